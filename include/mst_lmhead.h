@@ -1,0 +1,153 @@
+/*
+ * mst_lmhead.h -- C ABI of the mini-sequence LM-head + cross-entropy library
+ *                 (hand-written HIP for gfx950 / MI355X).
+ *
+ * The operation is the LM-head block of the Mini-Sequence Transformer paper:
+ * Algorithm 2 (forward) and Algorithm 4 (backward with logit recomputation).
+ * The token dimension S (the paper's N; batch folded in) is split into M
+ * mini-sequences of C = ceil(S / M) rows.  For chunk i
+ *
+ *     logits_i = H_i W^T                          (Algorithm 2, line 4)
+ *     loss    += sum of per-row NLL of chunk i    (Algorithm 2, line 6)
+ *
+ * and in the backward pass the chunk's logits are formed again and turned into
+ *
+ *     dlogits_i = (softmax(logits_i) - onehot(labels_i))        (Alg. 4, l. 5-6)
+ *     dH_i      = dlogits_i W          * grad_loss / N_valid    (Alg. 4, l. 7, 9)
+ *     dW       += dlogits_i^T H_i      * grad_loss / N_valid    (Alg. 4, l. 8, 10)
+ *
+ * so that only one C x V block of logits is alive at a time.  By the paper's
+ * exactness claim (Section 3.1) the result equals the standard head
+ * loss = crossentropy(H W^T, labels) of Theorem 4, for every M.
+ *
+ * Readings of the paper fixed by this interface:
+ *   - the loss is the mean over all non-ignored tokens of the whole call
+ *     (per-chunk sums, one division), which is the only reading of Algorithm 2
+ *     line 7 that is independent of M when chunks hold different numbers of
+ *     ignored labels;
+ *   - W is stored [V, d] row-major (a bias-free linear layer d -> V, as in the
+ *     paper's model listing), so logits = H W^T and dW is [V, d];
+ *   - the upstream gradient of Algorithm 4 multiplies once, not once per chunk;
+ *   - labels are already aligned with the rows of H (no causal shift here);
+ *   - the ignore value (-100 in Algorithm 2, line 5) is an argument.
+ *
+ * Conventions
+ *   - Every pointer named below is a DEVICE pointer owned by the caller, except
+ *     where "host" is written.  The library allocates no device memory and
+ *     keeps no state between calls (profiling events aside).
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*); the
+ *     calls return without waiting for the GPU.
+ *   - Return value: MST_OK (0) or a negative error code.  Argument errors are
+ *     found on the host before anything is launched.  A label outside [0, V)
+ *     that is not `ignore_index` is a data error found on the device: it never
+ *     causes an out-of-range access; the forward call then writes NaN to *loss
+ *     and -1 to *n_valid.
+ *   - Requirements: d % 8 == 0; H, W, dH 16-byte aligned; dW, lse 4-byte
+ *     aligned; workspace 256-byte aligned; 1 <= M <= S; V * d < 2^31;
+ *     ceil(S/M) * (V rounded up to 8) < 2^31.
+ *   - Arithmetic: bf16 operands, fp32 MFMA accumulation, fp32 log-sum-exp and
+ *     softmax, dlogits rounded to bf16 (nearest even) before the two gradient
+ *     GEMMs, dH rounded to bf16, dW fp32.  dW is accumulated chunk by chunk in
+ *     a fixed order without atomics: repeated calls give bit-identical dW.
+ *   - N_valid == 0: loss = 0, dH = 0, dW = 0.
+ */
+#ifndef MST_LMHEAD_H
+#define MST_LMHEAD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int mst_status;
+
+enum {
+  MST_OK = 0,
+  MST_ERR_NULL_POINTER = -1,   /* a required pointer is NULL                      */
+  MST_ERR_BAD_SHAPE = -2,      /* S, d or V <= 0, d % 8 != 0, or a size limit hit  */
+  MST_ERR_BAD_M = -3,          /* M < 1 or M > S                                  */
+  MST_ERR_WORKSPACE = -4,      /* workspace NULL or smaller than required          */
+  MST_ERR_ALIGNMENT = -5,      /* a pointer is not aligned as required             */
+  MST_ERR_LAUNCH = -6,         /* the HIP runtime refused a launch                 */
+  MST_ERR_NO_DEVICE = -7       /* no gfx950 device is current                      */
+};
+
+/* Human-readable text for a status code (host; static storage). */
+const char* mst_strerror(mst_status status);
+
+/* Library version string (host; static storage). */
+const char* mst_version(void);
+
+/*
+ * Workspace sizes in bytes for the forward and the backward call (host-only,
+ * launches nothing).  Either output pointer may be NULL.  The backward figure
+ * is for the case `lse` is supplied; without it the backward call first runs
+ * the forward's log-sum-exp pass and needs bwd_bytes + fwd_bytes + 4 * S
+ * rounded up to a multiple of 256.
+ * For the paper-shaped configurations both are below ceil(S/M) * V * 4 bytes,
+ * the size of one chunk of fp32 logits.
+ */
+mst_status mst_workspace_bytes(int64_t S, int64_t d, int64_t V, int32_t M,
+                               size_t* fwd_bytes, size_t* bwd_bytes);
+
+/*
+ * Forward: mini-sequence LM-head loss (Algorithm 2).
+ *   H        bf16 [S, d] row-major
+ *   W        bf16 [V, d] row-major
+ *   labels   int32 [S]; rows whose label equals ignore_index are skipped
+ *   loss     out, fp32 scalar: mean NLL over the non-ignored rows
+ *   lse      out, optional (may be NULL): fp32 [S], log-sum-exp of every row's
+ *            logits; pass it to the backward call to save one GEMM pass
+ *   n_valid  out, optional (may be NULL): int64 scalar, number of non-ignored rows
+ *   workspace / workspace_bytes   scratch of at least the forward size above
+ */
+mst_status mst_lmhead_ce_fwd(const void* H, const void* W, const int32_t* labels,
+                             int64_t S, int64_t d, int64_t V,
+                             int32_t ignore_index, int32_t M,
+                             void* workspace, size_t workspace_bytes,
+                             float* loss, float* lse, int64_t* n_valid,
+                             void* stream);
+
+/*
+ * Backward: mini-sequence LM-head gradients with recomputation (Algorithm 4).
+ *   grad_loss  upstream d(objective)/d(loss) (the algorithm's "nabla loss"), host value
+ *   lse        optional fp32 [S] from the forward call (NULL: recomputed here)
+ *   dH         out, bf16 [S, d], fully overwritten (ignored rows are exactly 0)
+ *   dW         out, fp32 [V, d], fully overwritten
+ */
+mst_status mst_lmhead_ce_bwd(const void* H, const void* W, const int32_t* labels,
+                             int64_t S, int64_t d, int64_t V,
+                             int32_t ignore_index, int32_t M,
+                             float grad_loss, const float* lse,
+                             void* workspace, size_t workspace_bytes,
+                             void* dH, float* dW,
+                             void* stream);
+
+/*
+ * Per-kernel timing (host).  When enabled, every kernel launch of the two calls
+ * above is bracketed by HIP events on the caller's stream.  mst_profile_collect
+ * waits for the recorded events, adds the elapsed milliseconds and launch
+ * counts per kernel kind into the caller's arrays (each of length
+ * MST_PROFILE_KINDS, indexed by the enum below) and clears the record.
+ */
+enum {
+  MST_K_LABEL_SCAN = 0,  /* N_valid, label range check                         */
+  MST_K_FWD_GEMM_LSE,    /* logits tile GEMM + running max / sum-exp epilogue   */
+  MST_K_LSE_FINALIZE,    /* combine per-vocab-tile partials into lse, nll       */
+  MST_K_LOSS_REDUCE,     /* fixed-order sum of nll / N_valid                    */
+  MST_K_BWD_GEMM_DLOGITS,/* recomputed logits GEMM + softmax-minus-onehot       */
+  MST_K_BWD_GEMM_DH,     /* dH_i = dlogits_i W (split over V)                   */
+  MST_K_BWD_DH_REDUCE,   /* fixed-order sum of the dH split partials            */
+  MST_K_BWD_GEMM_DW,     /* dW += dlogits_i^T H_i                               */
+  MST_PROFILE_KINDS
+};
+mst_status mst_profile_enable(int enable);
+mst_status mst_profile_collect(double* ms_per_kind, int64_t* launches_per_kind);
+const char* mst_profile_kind_name(int kind);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MST_LMHEAD_H */

@@ -1,0 +1,318 @@
+// Host side of the mini-sequence LM-head + cross-entropy library: argument
+// validation, the chunk schedule over the M mini-sequences (Algorithm 2 lines
+// 1-3 and Algorithm 4 lines 1-4 of the paper: partition, then loop), workspace
+// carving, launches, and the optional per-kernel event timing.
+#include "../../include/mst_lmhead.h"
+#include "mst_kernels.hpp"
+
+#include <mutex>
+#include <vector>
+
+namespace {
+
+using namespace mst;
+
+constexpr int kNumCu = 256;          // MI355X compute units; only steers the dH split choice
+constexpr int kMaxDhSplit = 16;
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct Plan {
+  int64_t S, d, V;
+  int M;
+  int C;            // rows per chunk = ceil(S / M)
+  int n_chunks;     // non-empty chunks = ceil(S / C)
+  int ldg;          // leading dimension of the dlogits workspace (V rounded up to 8)
+  int n_vt;         // vocabulary tiles
+  int n_jt;         // hidden tiles
+  int n_st;         // row tiles of a full chunk
+  int dh_split;     // splits of the dH contraction over V
+  int dh_ksteps;    // K steps (of kBK) per split
+  // forward workspace (byte offsets)
+  size_t f_nll, f_tgt, f_part, f_total;
+  // backward workspace
+  size_t b_g, b_partial, b_total;
+};
+
+mst_status make_plan(int64_t S, int64_t d, int64_t V, int32_t M, Plan* p) {
+  if (S <= 0 || d <= 0 || V <= 0) return MST_ERR_BAD_SHAPE;
+  if (d % 8 != 0) return MST_ERR_BAD_SHAPE;
+  if (M < 1 || (int64_t)M > S) return MST_ERR_BAD_M;
+  if (V * d >= (int64_t(1) << 31)) return MST_ERR_BAD_SHAPE;
+  const int64_t C = (S + M - 1) / M;
+  const int64_t ldg = (V + 7) / 8 * 8;
+  if (C * ldg >= (int64_t(1) << 31) || C * d >= (int64_t(1) << 31)) return MST_ERR_BAD_SHAPE;
+  p->S = S; p->d = d; p->V = V; p->M = M;
+  p->C = (int)C;
+  p->n_chunks = (int)((S + C - 1) / C);
+  p->ldg = (int)ldg;
+  p->n_vt = (int)((V + kTile - 1) / kTile);
+  p->n_jt = (int)((d + kTile - 1) / kTile);
+  p->n_st = (int)((C + kTile - 1) / kTile);
+  // dH: few output tiles, long contraction -> split V so that about one workgroup per CU exists
+  const int out_tiles = p->n_st * p->n_jt;
+  const int ksteps = (int)((V + kBK - 1) / kBK);
+  int split = (kNumCu + out_tiles / 2) / out_tiles;
+  if (split < 1) split = 1;
+  if (split > kMaxDhSplit) split = kMaxDhSplit;
+  if (split > ksteps) split = ksteps;
+  // keep dlogits + split partials inside the byte size of one fp32 logits chunk (C * V * 4)
+  {
+    const int64_t cap = C * V * 4, g_bytes = C * ldg * 2, per_split = C * d * 4;
+    const int64_t room = (cap - g_bytes - 1024) / per_split;
+    if (split > 1 && (int64_t)split > room) split = room >= 2 ? (int)room : 1;
+  }
+  p->dh_ksteps = (ksteps + split - 1) / split;
+  p->dh_split = (ksteps + p->dh_ksteps - 1) / p->dh_ksteps;
+
+  size_t off = sizeof(Control);
+  p->f_nll = off;  off = align_up(off + (size_t)S * 4, 256);
+  p->f_tgt = off;  off = align_up(off + (size_t)C * 4, 256);
+  p->f_part = off; off = align_up(off + (size_t)p->n_vt * C * 8, 256);
+  p->f_total = off;
+
+  off = sizeof(Control);
+  p->b_g = off;       off = align_up(off + (size_t)C * ldg * 2, 256);
+  p->b_partial = off; off = align_up(off + (p->dh_split > 1 ? (size_t)p->dh_split * C * d * 4 : 0), 256);
+  p->b_total = off;
+  return MST_OK;
+}
+
+// ------------------------------------------------------------------ profiling
+struct Profiler {
+  std::mutex mu;
+  bool enabled = false;
+  struct Rec { int kind; hipEvent_t a, b; };
+  std::vector<Rec> recs;
+  std::vector<hipEvent_t> pool;
+  hipEvent_t get() {
+    if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+  }
+};
+Profiler g_prof;
+
+struct Scope {   // brackets one launch with events when profiling is on
+  hipStream_t st; int kind; hipEvent_t a = nullptr, b = nullptr; bool on;
+  Scope(hipStream_t s, int k) : st(s), kind(k), on(g_prof.enabled) {
+    if (!on) return;
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    a = g_prof.get(); b = g_prof.get();
+    if (a) (void)hipEventRecord(a, st);
+  }
+  ~Scope() {
+    if (!on) return;
+    if (b) (void)hipEventRecord(b, st);
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    if (a && b) g_prof.recs.push_back({kind, a, b});
+  }
+};
+
+std::once_flag g_attr_once;
+hipError_t g_attr_err = hipSuccess;
+void set_kernel_attributes() {
+  auto set = [](const void* f) {
+    hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (e != hipSuccess && g_attr_err == hipSuccess) g_attr_err = e;
+  };
+  set((const void*)k_fwd_gemm_lse);
+  set((const void*)k_bwd_gemm_dlogits);
+  set((const void*)k_bwd_gemm_dh);
+  set((const void*)k_bwd_gemm_dw);
+}
+
+bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) != 0; }
+
+mst_status check_launch() { return hipGetLastError() == hipSuccess ? MST_OK : MST_ERR_LAUNCH; }
+
+mst_status prepare_device() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return MST_ERR_NO_DEVICE;
+  std::call_once(g_attr_once, set_kernel_attributes);
+  if (g_attr_err != hipSuccess) return MST_ERR_LAUNCH;
+  return MST_OK;
+}
+
+// forward pass over all chunks: writes lse (if non-null) and nll (if non-null)
+mst_status run_forward_chunks(const Plan& p, const __bf16* H, const __bf16* W, const int32_t* labels,
+                              int ignore_index, char* ws, float* lse, float* nll, hipStream_t st) {
+  float* tgt = reinterpret_cast<float*>(ws + p.f_tgt);
+  float2* part = reinterpret_cast<float2*>(ws + p.f_part);
+  for (int i = 0; i < p.n_chunks; ++i) {
+    const int64_t r0 = (int64_t)i * p.C;
+    const int rows = (int)((p.S - r0) < p.C ? (p.S - r0) : p.C);
+    const int n_st = (rows + kTile - 1) / kTile;
+    const __bf16* Hc = H + r0 * p.d;
+    {
+      Scope sc(st, MST_K_FWD_GEMM_LSE);
+      hipLaunchKernelGGL(k_fwd_gemm_lse, dim3(xcd_grid(n_st * p.n_vt)), dim3(kThreads), kLdsBytes, st,
+                         Hc, W, labels + r0, rows, (int)p.d, (int)p.V, n_st, p.n_vt, part, p.C, tgt);
+    }
+    {
+      Scope sc(st, MST_K_LSE_FINALIZE);
+      hipLaunchKernelGGL(k_lse_finalize, dim3((rows + 255) / 256), dim3(256), 0, st,
+                         part, p.C, p.n_vt, tgt, labels + r0, rows, (int)p.V, ignore_index,
+                         lse ? lse + r0 : nullptr, nll ? nll + r0 : nullptr);
+    }
+  }
+  return check_launch();
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* mst_strerror(mst_status s) {
+  switch (s) {
+    case MST_OK: return "ok";
+    case MST_ERR_NULL_POINTER: return "a required pointer is NULL";
+    case MST_ERR_BAD_SHAPE: return "bad shape: S, d, V must be positive, d % 8 == 0, V*d < 2^31, ceil(S/M)*V < 2^31";
+    case MST_ERR_BAD_M: return "M must satisfy 1 <= M <= S";
+    case MST_ERR_WORKSPACE: return "workspace is NULL or too small (see mst_workspace_bytes)";
+    case MST_ERR_ALIGNMENT: return "pointer alignment: H, W, dH 16 bytes; workspace 256 bytes; lse, dW 4 bytes";
+    case MST_ERR_LAUNCH: return "the HIP runtime refused a kernel launch or attribute";
+    case MST_ERR_NO_DEVICE: return "no current HIP device";
+    default: return "unknown status";
+  }
+}
+
+const char* mst_version(void) { return "mst-lmhead 0.1 (gfx950)"; }
+
+mst_status mst_workspace_bytes(int64_t S, int64_t d, int64_t V, int32_t M, size_t* fwd_bytes, size_t* bwd_bytes) {
+  Plan p;
+  mst_status s = make_plan(S, d, V, M, &p);
+  if (s != MST_OK) return s;
+  if (fwd_bytes) *fwd_bytes = p.f_total;
+  if (bwd_bytes) *bwd_bytes = p.b_total;
+  return MST_OK;
+}
+
+mst_status mst_lmhead_ce_fwd(const void* H, const void* W, const int32_t* labels, int64_t S, int64_t d, int64_t V,
+                             int32_t ignore_index, int32_t M, void* workspace, size_t workspace_bytes,
+                             float* loss, float* lse, int64_t* n_valid, void* stream) {
+  Plan p;
+  mst_status s = make_plan(S, d, V, M, &p);
+  if (s != MST_OK) return s;
+  if (!H || !W || !labels || !loss) return MST_ERR_NULL_POINTER;
+  if (!workspace || workspace_bytes < p.f_total) return MST_ERR_WORKSPACE;
+  if (misaligned(H, 16) || misaligned(W, 16) || misaligned(workspace, 256) || misaligned(lse, 4) ||
+      misaligned(labels, 4) || misaligned(loss, 4) || misaligned(n_valid, 8))
+    return MST_ERR_ALIGNMENT;
+  if ((s = prepare_device()) != MST_OK) return s;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  Control* ctl = reinterpret_cast<Control*>(ws);
+  float* nll = reinterpret_cast<float*>(ws + p.f_nll);
+  {
+    Scope sc(st, MST_K_LABEL_SCAN);
+    hipLaunchKernelGGL(k_label_scan, dim3(1), dim3(1024), 0, st, labels, (long long)S, (int)V, ignore_index, 1.0f, ctl);
+  }
+  s = run_forward_chunks(p, static_cast<const __bf16*>(H), static_cast<const __bf16*>(W), labels, ignore_index,
+                         ws, lse, nll, st);
+  if (s != MST_OK) return s;
+  {
+    Scope sc(st, MST_K_LOSS_REDUCE);
+    hipLaunchKernelGGL(k_loss_reduce, dim3(1), dim3(1024), 0, st, nll, (long long)S, ctl, loss,
+                       reinterpret_cast<long long*>(n_valid));
+  }
+  return check_launch();
+}
+
+mst_status mst_lmhead_ce_bwd(const void* H, const void* W, const int32_t* labels, int64_t S, int64_t d, int64_t V,
+                             int32_t ignore_index, int32_t M, float grad_loss, const float* lse,
+                             void* workspace, size_t workspace_bytes, void* dH, float* dW, void* stream) {
+  Plan p;
+  mst_status s = make_plan(S, d, V, M, &p);
+  if (s != MST_OK) return s;
+  if (!H || !W || !labels || !dH || !dW) return MST_ERR_NULL_POINTER;
+  const size_t need = lse ? p.b_total : p.b_total + p.f_total + align_up((size_t)S * 4, 256);
+  if (!workspace || workspace_bytes < need) return MST_ERR_WORKSPACE;
+  if (misaligned(H, 16) || misaligned(W, 16) || misaligned(dH, 16) || misaligned(workspace, 256) ||
+      misaligned(lse, 4) || misaligned(dW, 4) || misaligned(labels, 4))
+    return MST_ERR_ALIGNMENT;
+  if ((s = prepare_device()) != MST_OK) return s;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  Control* ctl = reinterpret_cast<Control*>(ws);
+  const __bf16* Hb = static_cast<const __bf16*>(H);
+  const __bf16* Wb = static_cast<const __bf16*>(W);
+  {
+    Scope sc(st, MST_K_LABEL_SCAN);
+    hipLaunchKernelGGL(k_label_scan, dim3(1), dim3(1024), 0, st, labels, (long long)S, (int)V, ignore_index, grad_loss, ctl);
+  }
+  if (!lse) {
+    // no saved log-sum-exp: run the forward's pass first, in the tail of the workspace
+    // (layout: [backward region | lse of S floats | forward region with its own unused control block])
+    float* lse_tmp = reinterpret_cast<float*>(ws + p.b_total);
+    char* fws = ws + p.b_total + align_up((size_t)S * 4, 256);
+    s = run_forward_chunks(p, Hb, Wb, labels, ignore_index, fws, lse_tmp, nullptr, st);
+    if (s != MST_OK) return s;
+    lse = lse_tmp;
+  }
+  __bf16* G = reinterpret_cast<__bf16*>(ws + p.b_g);
+  float* partial = reinterpret_cast<float*>(ws + p.b_partial);
+  __bf16* dHb = static_cast<__bf16*>(dH);
+  for (int i = 0; i < p.n_chunks; ++i) {
+    const int64_t r0 = (int64_t)i * p.C;
+    const int rows = (int)((p.S - r0) < p.C ? (p.S - r0) : p.C);
+    const int n_st = (rows + kTile - 1) / kTile;
+    const __bf16* Hc = Hb + r0 * p.d;
+    {
+      Scope sc(st, MST_K_BWD_GEMM_DLOGITS);
+      hipLaunchKernelGGL(k_bwd_gemm_dlogits, dim3(xcd_grid(n_st * p.n_vt)), dim3(kThreads), kLdsBytes, st,
+                         Hc, Wb, labels + r0, lse + r0, rows, (int)p.d, (int)p.V, ignore_index, n_st, p.n_vt, G, p.ldg);
+    }
+    {
+      Scope sc(st, MST_K_BWD_GEMM_DH);
+      hipLaunchKernelGGL(k_bwd_gemm_dh, dim3(xcd_grid(n_st * p.n_jt * p.dh_split)), dim3(kThreads), kLdsBytes, st,
+                         G, p.ldg, Wb, rows, (int)p.d, (int)p.V, n_st, p.n_jt, p.dh_split, p.dh_ksteps, ctl,
+                         partial, p.C, dHb + r0 * p.d);
+    }
+    if (p.dh_split > 1) {
+      Scope sc(st, MST_K_BWD_DH_REDUCE);
+      const size_t n = (size_t)rows * p.d;
+      hipLaunchKernelGGL(k_bwd_dh_reduce, dim3((unsigned)((n / 8 + 255) / 256)), dim3(256), 0, st,
+                         partial, p.dh_split, (size_t)p.C * p.d, n, ctl, dHb + r0 * p.d);
+    }
+    {
+      Scope sc(st, MST_K_BWD_GEMM_DW);
+      hipLaunchKernelGGL(k_bwd_gemm_dw, dim3(xcd_grid(p.n_vt * p.n_jt)), dim3(kThreads), kLdsBytes, st,
+                         G, p.ldg, Hc, rows, (int)p.d, (int)p.V, p.n_vt, p.n_jt, ctl, i > 0 ? 1 : 0, dW);
+    }
+  }
+  return check_launch();
+}
+
+mst_status mst_profile_enable(int enable) {
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  g_prof.enabled = enable != 0;
+  return MST_OK;
+}
+
+mst_status mst_profile_collect(double* ms_per_kind, int64_t* launches_per_kind) {
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  mst_status out = MST_OK;
+  for (auto& r : g_prof.recs) {
+    float ms = 0.f;
+    if (hipEventSynchronize(r.b) != hipSuccess || hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) out = MST_ERR_LAUNCH;
+    if (r.kind >= 0 && r.kind < MST_PROFILE_KINDS) {
+      if (ms_per_kind) ms_per_kind[r.kind] += ms;
+      if (launches_per_kind) launches_per_kind[r.kind] += 1;
+    }
+    g_prof.pool.push_back(r.a);
+    g_prof.pool.push_back(r.b);
+  }
+  g_prof.recs.clear();
+  return out;
+}
+
+const char* mst_profile_kind_name(int kind) {
+  static const char* names[MST_PROFILE_KINDS] = {
+      "label_scan", "fwd_gemm_lse", "lse_finalize", "loss_reduce",
+      "bwd_gemm_dlogits", "bwd_gemm_dh", "bwd_dh_reduce", "bwd_gemm_dw"};
+  return (kind >= 0 && kind < MST_PROFILE_KINDS) ? names[kind] : "?";
+}
+
+}  // extern "C"

@@ -1,0 +1,383 @@
+// Device kernels of the mini-sequence LM-head + cross-entropy path (gfx950).
+//
+// Per mini-sequence (chunk) of C rows, following Algorithm 2 (forward) and
+// Algorithm 4 (backward with recomputation) of the paper:
+//
+//   forward   k_fwd_gemm_lse     logits tile = W_tile H_chunk^T in MFMA accumulators; per row the
+//                                running max / sum-exp of the tile's 256 vocabulary entries and the
+//                                target logit are taken from the accumulators; no logits are stored
+//             k_lse_finalize     per row: combine the per-vocab-tile partials into lse, nll
+//   backward  k_bwd_gemm_dlogits logits tile again; softmax - onehot via the saved lse; bf16 to workspace
+//             k_bwd_gemm_dh      dH_chunk = dlogits W       (contraction over V, split, fixed-order reduce)
+//             k_bwd_gemm_dw      dW (+)= dlogits^T H_chunk  (contraction over the chunk's rows)
+//
+// All kernels use the 256 x 256 block tile main loop of gemm_tile.hpp.  The
+// linear workgroup id is remapped so that each of the 8 XCDs (which receive
+// workgroups round-robin and own a private L2) works on a contiguous range of
+// the tile space: workgroups that share an operand panel then share an L2.
+#pragma once
+#include "gemm_tile.hpp"
+
+namespace mst {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kMasked = -1.0e30f;     // stands for -infinity in max / sum-exp without producing NaN
+constexpr int kNumXcd = 8;
+
+// Control block at the start of the workspace, written by k_label_scan.
+struct Control {
+  long long n_valid;    // rows whose label is neither ignored nor out of range
+  int bad_labels;       // rows whose label is outside [0, V) and not the ignore value
+  float gamma;          // grad_loss / n_valid (0 when n_valid == 0)
+  float pad[60];
+};
+static_assert(sizeof(Control) == 256, "control block is one 256-byte line");
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// XCD-aware remap of the linear workgroup id to a work item; returns -1 for padding workgroups.
+__device__ __forceinline__ int xcd_work_item(int total) {
+  const int per_xcd = (total + kNumXcd - 1) / kNumXcd;
+  const int b = blockIdx.x;
+  const int w = (b % kNumXcd) * per_xcd + b / kNumXcd;
+  return w < total ? w : -1;
+}
+inline int xcd_grid(int total) { return kNumXcd * ((total + kNumXcd - 1) / kNumXcd); }
+
+// ---------------------------------------------------------------------------
+// label scan: N_valid, range check, gamma.  One workgroup, integer sums only.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void k_label_scan(const int* __restrict__ labels, long long S, int V,
+                                                     int ignore_index, float grad_loss, Control* ctl) {
+  __shared__ long long s_valid[16];
+  __shared__ int s_bad[16];
+  long long nv = 0;
+  int nb = 0;
+  for (long long i = threadIdx.x; i < S; i += 1024) {
+    const int y = labels[i];
+    if (y != ignore_index) {
+      if ((unsigned)y < (unsigned)V) ++nv; else ++nb;
+    }
+  }
+  for (int o = 32; o > 0; o >>= 1) {
+    nv += __shfl_xor(nv, o);
+    nb += __shfl_xor(nb, o);
+  }
+  if ((threadIdx.x & 63) == 0) { s_valid[threadIdx.x >> 6] = nv; s_bad[threadIdx.x >> 6] = nb; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    long long tv = 0; int tb = 0;
+    for (int i = 0; i < 16; ++i) { tv += s_valid[i]; tb += s_bad[i]; }
+    ctl->n_valid = tv;
+    ctl->bad_labels = tb;
+    ctl->gamma = tv > 0 ? (float)((double)grad_loss / (double)tv) : 0.f;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// forward: logits tile + running log-sum-exp partials + target logit
+//   A side = vocabulary (W rows), B side = chunk rows (H rows): a lane owns one
+//   row s and 16 consecutive vocabulary entries per MFMA tile, so the row
+//   reduction is in-lane plus one exchange with lane ^ 32.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void k_fwd_gemm_lse(
+    const __bf16* __restrict__ Hc, const __bf16* __restrict__ W, const int* __restrict__ labels_c,
+    int rows, int d, int V, int n_st, int n_vt, float2* __restrict__ part, int part_stride,
+    float* __restrict__ tgt) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const int w = xcd_work_item(n_st * n_vt);
+  if (w < 0) return;
+  const int vt = w / n_st, st = w - vt * n_st;
+  const int v0 = vt * kTile, s0 = st * kTile;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wa = wave >> 2, wb = wave & 3;
+
+  f32x16 acc[kTA][kTB];
+  zero_acc(acc);
+  PanelKC<kTA, true> pa;
+  PanelKC<kTB, false> pb;
+  pa.init(W + (size_t)v0 * d, d, V - v0, d, wave, lane, wa);
+  pb.init(Hc + (size_t)s0 * d, d, rows - s0, d, wave, lane, wb);
+  gemm_mainloop(acc, pa, pb, smem, 0, d);
+
+  const int va = v0 + wa * 128 + 16 * (lane >> 5);   // first vocabulary index of this lane in MFMA tile 0
+  if (v0 + kTile > V) {                              // ragged last vocabulary tile: mask entries >= V
+#pragma unroll
+    for (int t = 0; t < kTA; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (va + 32 * t + r >= V) {
+#pragma unroll
+          for (int u = 0; u < kTB; ++u) acc[t][u][r] = kMasked;
+        }
+  }
+
+  float2* xch = reinterpret_cast<float2*>(smem);     // [wb][u][32] pairs from the wa == 1 waves
+  float m_u[kTB], l_u[kTB];
+#pragma unroll
+  for (int u = 0; u < kTB; ++u) {
+    float m = kMasked;
+#pragma unroll
+    for (int t = 0; t < kTA; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) m = fmaxf(m, acc[t][u][r]);
+    float l = 0.f;
+    // subtract before scaling: with the masking sentinel, a fused (z * log2e - m * log2e)
+    // would leave a huge rounding residue when z == m == sentinel
+#pragma unroll
+    for (int t = 0; t < kTA; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) l += fast_exp2((acc[t][u][r] - m) * kLog2e);
+    const float m2 = __shfl_xor(m, 32), l2 = __shfl_xor(l, 32);
+    const float mm = fmaxf(m, m2);
+    l = l * fast_exp2((m - mm) * kLog2e) + l2 * fast_exp2((m2 - mm) * kLog2e);
+    m_u[u] = mm;
+    l_u[u] = l;
+
+    // target logit straight from the accumulator that holds it
+    const int s_local = s0 + wb * 64 + 32 * u + (lane & 31);
+    const int y = s_local < rows ? labels_c[s_local] : -1;
+    const int rel = y - (v0 + wa * 128);
+    if (rel >= 0 && rel < 128 && y < V && ((rel >> 4) & 1) == (lane >> 5)) {
+      const int t_sel = rel >> 5, r_sel = rel & 15;
+      float val = 0.f;
+#pragma unroll
+      for (int t = 0; t < kTA; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (t == t_sel && r == r_sel) val = acc[t][u][r];
+      tgt[s_local] = val;
+    }
+  }
+  // the main loop ended with a barrier, LDS is free
+  if (wa == 1 && lane < 32) {
+#pragma unroll
+    for (int u = 0; u < kTB; ++u) xch[(wb * kTB + u) * 32 + lane] = make_float2(m_u[u], l_u[u]);
+  }
+  __syncthreads();
+  if (wa == 0 && lane < 32) {
+#pragma unroll
+    for (int u = 0; u < kTB; ++u) {
+      const float2 o = xch[(wb * kTB + u) * 32 + lane];
+      const float mm = fmaxf(m_u[u], o.x);
+      const float l = l_u[u] * fast_exp2((m_u[u] - mm) * kLog2e) + o.y * fast_exp2((o.x - mm) * kLog2e);
+      const int s_local = s0 + wb * 64 + 32 * u + lane;
+      if (s_local < rows) part[(size_t)vt * part_stride + s_local] = make_float2(mm, l);
+    }
+  }
+}
+
+// per row: combine the vocab-tile partials in tile order; lse, nll
+__global__ __launch_bounds__(256) void k_lse_finalize(
+    const float2* __restrict__ part, int part_stride, int n_vt, const float* __restrict__ tgt,
+    const int* __restrict__ labels_c, int rows, int V, int ignore_index,
+    float* __restrict__ lse_c, float* __restrict__ nll_c) {
+  const int s = blockIdx.x * 256 + threadIdx.x;
+  if (s >= rows) return;
+  float m = kMasked, l = 0.f;
+  for (int vt = 0; vt < n_vt; ++vt) {
+    const float2 p = part[(size_t)vt * part_stride + s];
+    const float mm = fmaxf(m, p.x);
+    l = l * fast_exp2((m - mm) * kLog2e) + p.y * fast_exp2((p.x - mm) * kLog2e);
+    m = mm;
+  }
+  const float lse = m + __builtin_amdgcn_logf(l) * kLn2;   // v_log_f32 is log2
+  const int y = labels_c[s];
+  const bool valid = (y != ignore_index) && ((unsigned)y < (unsigned)V);
+  if (lse_c) lse_c[s] = lse;
+  if (nll_c) nll_c[s] = valid ? lse - tgt[s] : 0.f;
+}
+
+// loss = sum(nll) / n_valid, fixed summation order, fp64 accumulation.  One workgroup.
+__global__ __launch_bounds__(1024) void k_loss_reduce(const float* __restrict__ nll, long long S,
+                                                      const Control* __restrict__ ctl,
+                                                      float* __restrict__ loss, long long* __restrict__ n_valid_out) {
+  __shared__ double sh[1024];
+  double a = 0.0;
+  for (long long i = threadIdx.x; i < S; i += 1024) a += (double)nll[i];
+  sh[threadIdx.x] = a;
+  __syncthreads();
+  for (int o = 512; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) sh[threadIdx.x] += sh[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const long long nv = ctl->n_valid;
+    if (ctl->bad_labels > 0) {
+      *loss = __builtin_nanf("");
+      if (n_valid_out) *n_valid_out = -1;
+    } else {
+      *loss = nv > 0 ? (float)(sh[0] / (double)nv) : 0.f;
+      if (n_valid_out) *n_valid_out = nv;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// backward 1: recompute the logits tile, write softmax - onehot as bf16
+//   (the factor grad_loss / N_valid is applied in fp32 by the two gradient GEMMs)
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void k_bwd_gemm_dlogits(
+    const __bf16* __restrict__ Hc, const __bf16* __restrict__ W, const int* __restrict__ labels_c,
+    const float* __restrict__ lse_c, int rows, int d, int V, int ignore_index, int n_st, int n_vt,
+    __bf16* __restrict__ G, int ldg) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const int w = xcd_work_item(n_st * n_vt);
+  if (w < 0) return;
+  const int vt = w / n_st, st = w - vt * n_st;
+  const int v0 = vt * kTile, s0 = st * kTile;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wa = wave >> 2, wb = wave & 3;
+
+  f32x16 acc[kTA][kTB];
+  zero_acc(acc);
+  PanelKC<kTA, true> pa;
+  PanelKC<kTB, false> pb;
+  pa.init(W + (size_t)v0 * d, d, V - v0, d, wave, lane, wa);
+  pb.init(Hc + (size_t)s0 * d, d, rows - s0, d, wave, lane, wb);
+  gemm_mainloop(acc, pa, pb, smem, 0, d);
+
+  const int va = v0 + wa * 128 + 16 * (lane >> 5);
+#pragma unroll
+  for (int u = 0; u < kTB; ++u) {
+    const int s_local = s0 + wb * 64 + 32 * u + (lane & 31);
+    if (s_local >= rows) continue;
+    const int y = labels_c[s_local];
+    const bool valid = (y != ignore_index) && ((unsigned)y < (unsigned)V);
+    const float lb = lse_c[s_local] * kLog2e;
+    __bf16* grow = G + (size_t)s_local * ldg;
+#pragma unroll
+    for (int t = 0; t < kTA; ++t) {
+      const int vb = va + 32 * t;
+      bf16x8 lo, hi;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int v = vb + r;
+        float g = fast_exp2(acc[t][u][r] * kLog2e - lb);
+        if (v == y) g -= 1.0f;
+        if (!valid || v >= V) g = 0.f;
+        if (r < 8) lo[r] = (__bf16)g; else hi[r - 8] = (__bf16)g;
+      }
+      if (vb < ldg) *reinterpret_cast<bf16x8*>(grow + vb) = lo;
+      if (vb + 8 < ldg) *reinterpret_cast<bf16x8*>(grow + vb + 8) = hi;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// backward 2: dH_chunk = G W over a range of the vocabulary
+//   A side = chunk rows (G, K-contiguous), B side = hidden index j (W, K-strided)
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void k_bwd_gemm_dh(
+    const __bf16* __restrict__ G, int ldg, const __bf16* __restrict__ W, int rows, int d, int V,
+    int n_st, int n_jt, int n_split, int ksteps_per_split, const Control* __restrict__ ctl,
+    float* __restrict__ partial /* [n_split][rows_stride][d], used when n_split > 1 */, int rows_stride,
+    __bf16* __restrict__ dHc /* used when n_split == 1 */) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const int w = xcd_work_item(n_st * n_jt * n_split);
+  if (w < 0) return;
+  const int st = w % n_st;
+  const int jt = (w / n_st) % n_jt;
+  const int sp = w / (n_st * n_jt);
+  const int s0 = st * kTile, j0 = jt * kTile;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wa = wave >> 2, wb = wave & 3;
+  const int k_begin = sp * ksteps_per_split * kBK;
+  int k_end = k_begin + ksteps_per_split * kBK;
+  if (k_end > V) k_end = V;
+
+  f32x16 acc[kTA][kTB];
+  zero_acc(acc);
+  PanelKC<kTA, false> pa;
+  PanelKS<kTB> pb;
+  pa.init(G + (size_t)s0 * ldg, ldg, rows - s0, ldg, wave, lane, wa);
+  pb.init(W + j0, d, V, d - j0, wave, lane, wb);
+  gemm_mainloop(acc, pa, pb, smem, k_begin, k_end);
+
+  const float gamma = ctl->gamma;
+#pragma unroll
+  for (int t = 0; t < kTA; ++t)
+#pragma unroll
+    for (int u = 0; u < kTB; ++u) {
+      const int j = j0 + wb * 64 + 32 * u + (lane & 31);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int s_local = s0 + wa * 128 + 32 * t + a_index_in_tile<false>(r, lane);
+        if (s_local < rows && j < d) {
+          if (n_split > 1) partial[((size_t)sp * rows_stride + s_local) * d + j] = acc[t][u][r];
+          else dHc[(size_t)s_local * d + j] = (__bf16)(gamma * acc[t][u][r]);
+        }
+      }
+    }
+}
+
+// fixed-order sum over the splits, scale, round to bf16.  8 outputs per thread.
+__global__ __launch_bounds__(256) void k_bwd_dh_reduce(const float* __restrict__ partial, int n_split,
+                                                       size_t split_stride /* rows_stride * d */, size_t n /* rows * d */,
+                                                       const Control* __restrict__ ctl, __bf16* __restrict__ dHc) {
+  const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 8;
+  if (i >= n) return;
+  const float gamma = ctl->gamma;
+  float4 a0 = *reinterpret_cast<const float4*>(partial + i);
+  float4 a1 = *reinterpret_cast<const float4*>(partial + i + 4);
+  for (int sp = 1; sp < n_split; ++sp) {
+    const float4 b0 = *reinterpret_cast<const float4*>(partial + sp * split_stride + i);
+    const float4 b1 = *reinterpret_cast<const float4*>(partial + sp * split_stride + i + 4);
+    a0.x += b0.x; a0.y += b0.y; a0.z += b0.z; a0.w += b0.w;
+    a1.x += b1.x; a1.y += b1.y; a1.z += b1.z; a1.w += b1.w;
+  }
+  bf16x8 o;
+  o[0] = (__bf16)(gamma * a0.x); o[1] = (__bf16)(gamma * a0.y); o[2] = (__bf16)(gamma * a0.z); o[3] = (__bf16)(gamma * a0.w);
+  o[4] = (__bf16)(gamma * a1.x); o[5] = (__bf16)(gamma * a1.y); o[6] = (__bf16)(gamma * a1.z); o[7] = (__bf16)(gamma * a1.w);
+  *reinterpret_cast<bf16x8*>(dHc + i) = o;
+}
+
+// ---------------------------------------------------------------------------
+// backward 3: dW (+)= G^T H_chunk, contraction over the chunk's rows
+//   A side = vocabulary (G columns, K-strided), B side = hidden index j (H columns, K-strided)
+//   dW is fp32 and is its own accumulator: chunk 0 writes, later chunks read-modify-write,
+//   always in chunk order on one stream, so the sum order is fixed.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void k_bwd_gemm_dw(
+    const __bf16* __restrict__ G, int ldg, const __bf16* __restrict__ Hc, int rows, int d, int V,
+    int n_vt, int n_jt, const Control* __restrict__ ctl, int accumulate, float* __restrict__ dW) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const int w = xcd_work_item(n_vt * n_jt);
+  if (w < 0) return;
+  const int vt = w / n_jt, jt = w - vt * n_jt;
+  const int v0 = vt * kTile, j0 = jt * kTile;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wa = wave >> 2, wb = wave & 3;
+
+  f32x16 acc[kTA][kTB];
+  zero_acc(acc);
+  PanelKS<kTA> pa;
+  PanelKS<kTB> pb;
+  pa.init(G + v0, ldg, rows, ldg - v0, wave, lane, wa);
+  pb.init(Hc + j0, d, rows, d - j0, wave, lane, wb);
+  gemm_mainloop(acc, pa, pb, smem, 0, rows);
+
+  const float gamma = ctl->gamma;
+#pragma unroll
+  for (int t = 0; t < kTA; ++t)
+#pragma unroll
+    for (int u = 0; u < kTB; ++u) {
+      const int j = j0 + wb * 64 + 32 * u + (lane & 31);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int v = v0 + wa * 128 + 32 * t + a_index_in_tile<false>(r, lane);
+        if (v < V && j < d) {
+          float* p = dW + (size_t)v * d + j;
+          const float x = gamma * acc[t][u][r];
+          *p = accumulate ? *p + x : x;
+        }
+      }
+    }
+}
+
+}  // namespace mst
