@@ -1,0 +1,172 @@
+#!/usr/bin/env python3
+"""Benchmark of the mini-sequence LM-head + cross-entropy path on one MI355X.
+
+One "step" is one forward call plus one backward call (with logit
+recomputation) over one batch of seeded synthetic input that is already
+resident in HBM.  The workload is the Llama3-8B-shaped configuration
+(S=8192, d=4096, V=128256, M=8).  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
+
+GEMM_KINDS = ("fwd_gemm_lse", "bwd_gemm_dlogits", "bwd_gemm_dh", "bwd_gemm_dw")
+
+
+def cpu_baseline(inp, sample_rows: int):
+    """The fp64 oracle as it stands, timed on the host cores on the first `sample_rows` tokens."""
+    import numpy as np
+    from oracle import lmhead_ce_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    rows = np.arange(min(sample_rows, inp.cfg.S))
+    H = inp.H_f64(rows)
+    W = inp.W_f64()
+    t0 = time.perf_counter()
+    r = orc.lmhead_ce(H, W, inp.labels[rows], inp.ignore_index)
+    dt = time.perf_counter() - t0
+    flops = 6.0 * len(rows) * inp.cfg.d * inp.cfg.V       # forward + dH + dW, no recomputation
+    return {
+        "value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+        "sample": f"first {len(rows)} of {inp.cfg.S} tokens of the same workload, full V and d, fp64 numpy "
+                  f"(loss+dH+dW = 6*S*d*V flop), {dt:.1f} s wall",
+        "seconds": dt, "loss_on_sample": r["loss"],
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--cpu-sample-rows", type=int, default=384)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true",
+                    help="do not bracket kernels with events inside the timed region")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import mst_inputs as mi
+    import paper_2407_15892_amd as mst
+    from tests.gpu_harness import to_device_bf16
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 2
+    mst.load_library()
+    cfg = mi.CONFIGS[args.config]
+    t0 = time.perf_counter()
+    inp = mi.make_inputs(cfg)
+    gen_s = time.perf_counter() - t0
+    S, d, V, M = cfg.S, cfg.d, cfg.V, cfg.M
+
+    H = to_device_bf16(inp.H_bits)
+    W = to_device_bf16(inp.W_bits)
+    labels = torch.from_numpy(inp.labels).cuda()
+    fwd_bytes, bwd_bytes = mst.mst_workspace_bytes(S, d, V, M)
+    ws = torch.empty(max(fwd_bytes, bwd_bytes), dtype=torch.uint8, device="cuda")
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    lse = torch.empty(S, dtype=torch.float32, device="cuda")
+    nv = torch.zeros(1, dtype=torch.int64, device="cuda")
+    dH = torch.empty((S, d), dtype=torch.bfloat16, device="cuda")
+    dW = torch.empty((V, d), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step():
+        mst.mst_lmhead_ce_fwd(H, W, labels, inp.ignore_index, M, ws, loss, lse, nv, stream)
+        mst.mst_lmhead_ce_bwd(H, W, labels, inp.ignore_index, M, 1.0, lse, ws, dH, dW, stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # separate forward / backward split (untimed for the headline, reported for information)
+    e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    e[0].record(stream)
+    mst.mst_lmhead_ce_fwd(H, W, labels, inp.ignore_index, M, ws, loss, lse, nv, stream)
+    e[1].record(stream)
+    mst.mst_lmhead_ce_bwd(H, W, labels, inp.ignore_index, M, 1.0, lse, ws, dH, dW, stream)
+    e[2].record(stream)
+    torch.cuda.synchronize()
+    fwd_ms, bwd_ms = e[0].elapsed_time(e[1]), e[1].elapsed_time(e[2])
+
+    timing = not args.no_kernel_timing
+    mst.mst_profile_enable(timing)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    kern = mst.mst_profile_collect() if timing else {}
+    mst.mst_profile_enable(False)
+
+    ms_per_step = dt * 1e3 / args.steps
+    f_exec = 8.0 * S * d * V                      # fwd GEMM + recompute + dH + dW
+    tflops = f_exec / (ms_per_step * 1e-3) / 1e12
+
+    # roofline of the dominant kernel (largest share of the timed region)
+    roofline = None
+    kernels = {}
+    if kern:
+        for k, (ms, n) in kern.items():
+            if n:
+                kernels[k] = {"launches": n, "avg_ms": ms / n, "total_ms_per_step": ms / args.steps}
+        dom = max(GEMM_KINDS, key=lambda k: kern[k][0])
+        ms, n = kern[dom]
+        C = cfg.C
+        flop_per_launch = 2.0 * C * d * V           # one chunk's GEMM: C x d x V multiply-adds
+        achieved = flop_per_launch / (ms / n * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+                    "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                    "flop_per_launch": flop_per_launch, "avg_launch_ms": ms / n}
+        for k in GEMM_KINDS:
+            ms_k, n_k = kern[k]
+            if n_k:
+                kernels[k]["tflops"] = flop_per_launch / (ms_k / n_k * 1e-3) / 1e12
+
+    out = {
+        "metric": "LM-head+CE fwd+bwd TFLOP/s (8*S*d*V executed flop incl. recomputation)",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"config {cfg.index} {cfg.name}: S={S} d={d} V={V} M={M} (C={cfg.C}), "
+                               f"bf16 H/W, int32 labels, fwd+bwd with logit recomputation",
+                   "S": S, "d": d, "V": V, "M": M},
+        "frac_of_bf16_peak": tflops / PEAK_BF16_TFLOPS,
+        "tflops_6SdV_convention": 6.0 * S * d * V / (ms_per_step * 1e-3) / 1e12,
+        "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
+        "peak_workspace_bytes": {"fwd": fwd_bytes, "bwd": bwd_bytes, "cap_one_fp32_logits_chunk": cfg.C * V * 4},
+        "loss": float(loss.item()), "n_valid": int(nv.item()),
+        "roofline": roofline, "kernels": kernels, "input_generation_s": gen_s,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(inp, args.cpu_sample_rows)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -9,6 +9,13 @@
 // The wave grid is 2 (A side) x 4 (B side): a wave accumulates 128 x 64, i.e.
 // 4 x 2 MFMA tiles = 128 fp32 accumulator registers per lane.
 //
+// The two halves of the workgroup (waves 0-3 and 4-7, one wave of each half on
+// every SIMD) run half a step apart: while one half reads its fragments of a
+// stage out of LDS and issues the global loads of a later stage, the other
+// half issues that stage's 32 MFMAs from registers; one workgroup barrier per
+// phase keeps them alternating, so the matrix pipe of a SIMD is fed by one
+// wave while its sibling waits on memory.
+//
 // "A side" is the index that ends up spread over a lane's 16 accumulator
 // registers, "B side" the index that ends up across the 32 lanes of a half
 // wave.  Either operand may be stored K-contiguous (layout KC: X[index][k]) or
@@ -18,7 +25,8 @@
 //
 // Buffer resources give hardware range checking: a lane whose address lies
 // beyond the matrix reads zeros instead of faulting, which is how ragged tile
-// edges are handled without branches.
+// edges are handled without branches, and why loads may be issued past the
+// end of K (they write zeros into a stage nobody reads).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -30,192 +38,254 @@ typedef __attribute__((ext_vector_type(4))) short i16x4;
 typedef __attribute__((ext_vector_type(8))) short i16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-constexpr int kTile = 256;                   // block tile extent on both sides
-constexpr int kBK = 64;                      // K step per LDS stage
-constexpr int kThreads = 512;
-constexpr int kPanelBytes = kTile * kBK * 2; // 32 KiB per operand per stage
-constexpr int kStageBytes = 2 * kPanelBytes; // A panel then B panel
-constexpr int kLdsBytes = 2 * kStageBytes;   // double buffered: 128 KiB
-constexpr int kTA = 4;                       // MFMA tiles per wave, A side (128 rows)
-constexpr int kTB = 2;                       // MFMA tiles per wave, B side (64 cols)
-constexpr uint32_t kOutOfRange = 0xFFFFFF00u;  // byte offset beyond any buffer we describe
+constexpr uint32_t kOutOfRange = 0xFFFFFF00u;
 
-// raw buffer resource: base address, no stride, byte count, 32-bit data format
+template <int WA_, int WB_, int TA_, int TB_, int BK_, int NS_>
+struct Cfg {
+  static constexpr int WA = WA_, WB = WB_, TA = TA_, TB = TB_, BK = BK_, NS = NS_;
+  static constexpr int kWaves = WA * WB, kThreads = 64 * kWaves;
+  static constexpr int EA = 32 * TA * WA, EB = 32 * TB * WB;
+  static constexpr int kPanelA = EA * BK * 2, kPanelB = EB * BK * 2;
+  static constexpr int kStage = kPanelA + kPanelB, kLds = NS * kStage;
+  static constexpr int kKK = BK / 16;
+};
+
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
 }
-
-// 16 bytes per lane from global memory into LDS at (m0 base + lane * 16).
 __device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t rsrc, uint32_t voffset, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                :: "s"(lds_addr), "v"(voffset), "s"(rsrc) : "memory");
 }
-
-__device__ __forceinline__ void wait_all_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-
+template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
 __device__ __forceinline__ uint32_t lds_addr_of(const void* p) {
   return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
 }
-
-// Which index of a 32-wide MFMA tile the A-side row `i` (0..31) stands for.
-// With `permute`, a lane's 16 accumulator registers cover 16 consecutive
-// indices (16*(lane/32) + r) instead of the native 8*(r/4) + 4*(lane/32) + r%4,
-// so that an epilogue can store 16 consecutive outputs per lane.
-template <bool kPermute>
-__device__ __forceinline__ int a_row_of_mfma_row(int i) {
+template <bool kPermute> __device__ __forceinline__ int a_row_of_mfma_row(int i) {
   if (!kPermute) return i;
   return 16 * ((i >> 2) & 1) + 4 * (i >> 3) + (i & 3);
 }
-template <bool kPermute>
-__device__ __forceinline__ int a_index_in_tile(int r, int lane) {   // accumulator register r -> A index within the 32-tile
+template <bool kPermute> __device__ __forceinline__ int a_index_in_tile(int r, int lane) {
   if (kPermute) return 16 * (lane >> 5) + r;
   return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
 }
 
-// ---------------------------------------------------------------------------
-// K-contiguous operand: X[index][k], row stride ld elements.  LDS panel is
-// [256 rows][64 k] with the eight 16-byte chunks of a row XOR-swizzled by
-// (row % 8), which makes the b128 fragment reads bank-conflict free.
-// ---------------------------------------------------------------------------
-template <int kTilesPerWave, bool kPermute>
+// K-contiguous panel [EXT rows][BK k]; LDS row = MFMA row order (a permutation, if any, is applied at the source)
+template <class C, int EXT, int TILES, bool kPermute>
 struct PanelKC {
+  static constexpr int BK = C::BK;
+  static constexpr int RB = BK * 2;             // bytes per LDS row
+  static constexpr int CPR = BK / 8;            // 16-byte chunks per row
+  static constexpr int RPS = 1024 / RB;         // rows per 1 KiB slot
+  static constexpr int NSLOT = EXT / RPS;
+  static constexpr int SPW = NSLOT / C::kWaves; // slots per wave
+  static_assert(NSLOT % C::kWaves == 0, "slots must divide over waves");
+  static constexpr int kBytes = EXT * RB;
   __amdgpu_buffer_rsrc_t rsrc;
-  uint32_t voff[4];   // this lane's global byte offset for k0 = 0, per issue slot
-  uint32_t kelem;     // k element index of this lane's chunk within the stage
-  uint32_t k_limit;   // number of valid k elements
-  uint32_t slot0;     // wave-uniform: first 1 KiB slot of this wave in the panel
-  uint32_t rd[4];     // fragment byte offsets within the panel, per k sub-step, tile 0
+  uint32_t voff[SPW];
+  uint32_t kelem[SPW];
+  uint32_t k_limit, slot0;
+  uint32_t rd[C::kKK];
 
-  // base: first row of the block's tile, k = 0.  rows_valid: rows of the matrix from there on.
-  __device__ __forceinline__ void init(const void* base, uint32_t ld_elems, uint32_t rows_valid,
-                                       uint32_t k_elems, int wave, int lane, int wave_side_index) {
+  // XOR swizzle of the 16-byte chunk index.  ds_read_b128 serves 16 lanes (256 bytes, all 64 banks)
+  // per clock; the 16 lanes of a quarter wave read 16 consecutive rows at one logical chunk, so
+  // the chunk index is XORed with the row bits that do not already select a bank.
+  __device__ __forceinline__ static int swz(int row) { return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
+
+  __device__ __forceinline__ void init(const void* base, uint32_t ld_elems, uint32_t rows_valid, uint32_t k_elems,
+                                       int wave, int lane, int wave_side_index) {
     const uint32_t ld_bytes = ld_elems * 2;
-    const uint32_t rows = rows_valid < (uint32_t)kTile ? rows_valid : (uint32_t)kTile;
+    const uint32_t rows = rows_valid < (uint32_t)EXT ? rows_valid : (uint32_t)EXT;
     rsrc = make_rsrc(base, rows * ld_bytes);
     k_limit = k_elems;
-    slot0 = wave * 4;
-    const int chunk = (lane & 7) ^ (lane >> 3);
-    kelem = chunk * 8;
+    slot0 = wave * SPW;
+    const int rin = lane / CPR, p = lane % CPR;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const uint32_t row = 8 * (slot0 + i) + (lane >> 3);
-      voff[i] = row * ld_bytes + chunk * 16;
+    for (int i = 0; i < SPW; ++i) {
+      const uint32_t lrow = RPS * (slot0 + i) + rin;                                   // LDS row
+      const uint32_t grow = (lrow & ~31u) + a_row_of_mfma_row<kPermute>(lrow & 31);    // global row
+      const int chunk = p ^ swz(lrow);
+      kelem[i] = chunk * 8;
+      voff[i] = grow * ld_bytes + chunk * 16;
     }
-    const int row0 = wave_side_index * (32 * kTilesPerWave) + a_row_of_mfma_row<kPermute>(lane & 31);
+    const int row0 = wave_side_index * (32 * TILES) + (lane & 31);
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) rd[kk] = row0 * 128 + (((2 * kk + (lane >> 5)) ^ (row0 & 7)) * 16);
+    for (int kk = 0; kk < C::kKK; ++kk) rd[kk] = row0 * RB + (((2 * kk + (lane >> 5)) ^ swz(row0)) * 16);
   }
   __device__ __forceinline__ void issue(uint32_t panel_lds, uint32_t k0) const {
-    const bool ok = (k0 + kelem) < k_limit;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      dma16(rsrc, ok ? voff[i] + k0 * 2 : kOutOfRange, panel_lds + (slot0 + i) * 1024);
+    for (int i = 0; i < SPW; ++i)
+      dma16(rsrc, (k0 + kelem[i]) < k_limit ? voff[i] + k0 * 2 : kOutOfRange, panel_lds + (slot0 + i) * 1024);
   }
   __device__ __forceinline__ bf16x8 frag(const char* panel, int t, int kk) const {
-    return *reinterpret_cast<const bf16x8*>(panel + rd[kk] + t * 4096);
+    return *reinterpret_cast<const bf16x8*>(panel + rd[kk] + t * (32 * RB));
   }
 };
 
-// ---------------------------------------------------------------------------
-// K-strided operand: X[k][index], row stride ld elements.  LDS panel is
-// [64 k][256 index]; the 16-byte chunks of row k are XOR-swizzled by
-// 2 * (k % 4) so that the four k rows a transposing read touches fall into
-// four different 32-byte bank groups.
-// ---------------------------------------------------------------------------
-template <int kTilesPerWave>
+// K-strided panel [BK k][EXT index]
+template <class C, int EXT, int TILES>
 struct PanelKS {
+  static constexpr int BK = C::BK;
+  static constexpr int RB = EXT * 2;
+  static constexpr int CPR = EXT / 8;
+  static constexpr int RPS = 1024 / RB;         // k rows per slot
+  static constexpr int NSLOT = BK / RPS;
+  static constexpr int SPW = NSLOT / C::kWaves;
+  static_assert(NSLOT % C::kWaves == 0, "slots must divide over waves");
+  static constexpr int kBytes = BK * RB;
   __amdgpu_buffer_rsrc_t rsrc;
-  uint32_t voff[4];   // this lane's global byte offset for k0 = 0, per issue slot
-  uint32_t ok_mask;   // bit i: the chunk of issue slot i lies inside the matrix' columns
-  uint32_t ld_bytes;
-  uint32_t slot0;
-  uint32_t rd[kTilesPerWave];
+  uint32_t voff[SPW];
+  uint32_t ok_mask, ld_bytes, slot0;
+  uint32_t rd[TILES];
 
-  // base: &X[0][col0].  k_rows: rows of X.  cols_valid: columns of X from col0 on
-  // (columns at or beyond it read as zero).
-  __device__ __forceinline__ void init(const void* base, uint32_t ld_elems, uint32_t k_rows,
-                                       uint32_t cols_valid, int wave, int lane, int wave_side_index) {
+  __device__ __forceinline__ void init(const void* base, uint32_t ld_elems, uint32_t k_rows, uint32_t cols_valid,
+                                       int wave, int lane, int wave_side_index) {
     ld_bytes = ld_elems * 2;
     const uint32_t last_cols = cols_valid < ld_elems ? cols_valid : ld_elems;
     rsrc = make_rsrc(base, (k_rows - 1) * ld_bytes + last_cols * 2);
-    slot0 = wave * 4;
+    slot0 = wave * SPW;
     ok_mask = 0;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const uint32_t krow = 2 * (slot0 + i) + (lane >> 5);
-      const uint32_t chunk = (lane & 31) ^ (2 * (krow & 3));
+    for (int i = 0; i < SPW; ++i) {
+      const uint32_t krow = RPS * (slot0 + i) + lane / CPR;
+      const uint32_t chunk = (lane % CPR) ^ (2 * (krow & 3));
       voff[i] = krow * ld_bytes + chunk * 16;
       ok_mask |= ((chunk * 8) < cols_valid ? 1u : 0u) << i;
     }
     const int g = lane >> 4, i16 = lane & 15;
 #pragma unroll
-    for (int t = 0; t < kTilesPerWave; ++t) {
-      const int col = wave_side_index * (32 * kTilesPerWave) + 32 * t + 16 * (g & 1) + 4 * (i16 & 3);
+    for (int t = 0; t < TILES; ++t) {
+      const int col = wave_side_index * (32 * TILES) + 32 * t + 16 * (g & 1) + 4 * (i16 & 3);
       const int krow = 8 * (g >> 1) + (i16 >> 2);
-      rd[t] = krow * 512 + (((col >> 3) ^ (2 * (i16 >> 2))) * 16) + (col & 7) * 2;
+      rd[t] = krow * RB + (((col >> 3) ^ (2 * (i16 >> 2))) * 16) + (col & 7) * 2;
     }
   }
   __device__ __forceinline__ void issue(uint32_t panel_lds, uint32_t k0) const {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < SPW; ++i)
       dma16(rsrc, ((ok_mask >> i) & 1u) ? voff[i] + k0 * ld_bytes : kOutOfRange, panel_lds + (slot0 + i) * 1024);
   }
-  // lane l receives index (l % 32) of tile t and k = 16 kk + 8 (l / 32) + 0..7, the MFMA operand layout
   __device__ __forceinline__ bf16x8 frag(const char* panel, int t, int kk) const {
     typedef __attribute__((address_space(3))) i16x4* lds_i16x4_ptr;
-    const char* p = panel + rd[t] + kk * (16 * 512);
+    const char* p = panel + rd[t] + kk * (16 * RB);
     i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)(p));
-    i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)(p + 4 * 512));
+    i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)(p + 4 * RB));
     i16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, v);
   }
 };
 
-// ---------------------------------------------------------------------------
-// Main loop: acc[t][u] += A-panel tile t  x  B-panel tile u over K.
-// ---------------------------------------------------------------------------
-template <class PanelA, class PanelB>
-__device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[kTA][kTB], const PanelA& pa, const PanelB& pb,
+// simple multi-stage loop: one barrier per K step, DMA issued NS-1 steps ahead (always issued; past the
+// end of K the loads are out of range and write zeros into a stage nobody reads)
+template <class C, class PA, class PB>
+__device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[C::TA][C::TB], const PA& pa, const PB& pb,
                                               char* smem, int k_begin, int k_end) {
+  constexpr int LPW = PA::SPW + PB::SPW;
   const uint32_t lds0 = lds_addr_of(smem);
-  const int nk = (k_end - k_begin + kBK - 1) / kBK;
-  if (nk <= 0) return;
-  pa.issue(lds0, k_begin);
-  pb.issue(lds0 + kPanelBytes, k_begin);
-  wait_all_loads();
-  __syncthreads();
+  const int nk = (k_end - k_begin + C::BK - 1) / C::BK;
+#pragma unroll
+  for (int s = 0; s < C::NS - 1; ++s) {
+    pa.issue(lds0 + s * C::kStage, k_begin + s * C::BK);
+    pb.issue(lds0 + s * C::kStage + C::kPanelA, k_begin + s * C::BK);
+  }
+  int cur = 0;                       // stage index of step kt
   for (int kt = 0; kt < nk; ++kt) {
-    const int cur = (kt & 1) * kStageBytes;
-    if (kt + 1 < nk) {
-      const int nxt = kStageBytes - cur;
-      pa.issue(lds0 + nxt, k_begin + (kt + 1) * kBK);
-      pb.issue(lds0 + nxt + kPanelBytes, k_begin + (kt + 1) * kBK);
+    wait_vmcnt<(C::NS - 2) * LPW>();
+    __syncthreads();
+    {
+      int nxt = cur + C::NS - 1; if (nxt >= C::NS) nxt -= C::NS;
+      const int k0 = k_begin + (kt + C::NS - 1) * C::BK;
+      pa.issue(lds0 + nxt * C::kStage, k0);
+      pb.issue(lds0 + nxt * C::kStage + C::kPanelA, k0);
     }
-    const char* a_panel = smem + cur;
-    const char* b_panel = smem + cur + kPanelBytes;
+    const char* a_panel = smem + cur * C::kStage;
+    const char* b_panel = a_panel + C::kPanelA;
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      bf16x8 a[kTA], b[kTB];
+    for (int kk = 0; kk < C::kKK; ++kk) {
+      bf16x8 a[C::TA], b[C::TB];
 #pragma unroll
-      for (int t = 0; t < kTA; ++t) a[t] = pa.frag(a_panel, t, kk);
+      for (int t = 0; t < C::TA; ++t) a[t] = pa.frag(a_panel, t, kk);
 #pragma unroll
-      for (int u = 0; u < kTB; ++u) b[u] = pb.frag(b_panel, u, kk);
+      for (int u = 0; u < C::TB; ++u) b[u] = pb.frag(b_panel, u, kk);
 #pragma unroll
-      for (int t = 0; t < kTA; ++t)
+      for (int t = 0; t < C::TA; ++t)
 #pragma unroll
-        for (int u = 0; u < kTB; ++u)
+        for (int u = 0; u < C::TB; ++u)
           acc[t][u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[t], b[u], acc[t][u], 0, 0, 0);
     }
-    wait_all_loads();
-    __syncthreads();
+    cur = cur + 1 == C::NS ? 0 : cur + 1;
   }
+  wait_vmcnt<0>();
+  __syncthreads();
 }
 
-__device__ __forceinline__ void zero_acc(f32x16 (&acc)[kTA][kTB]) {
+// ping-pong loop for 8 waves (WA == 2): waves 0-3 and 4-7 alternate between a memory phase (DMA issue +
+// all fragment reads of a stage) and a compute phase (all MFMAs of the stage), one barrier per phase
+template <class C, class PA, class PB>
+__device__ __forceinline__ void gemm_mainloop_pp(f32x16 (&acc)[C::TA][C::TB], const PA& pa, const PB& pb,
+                                                 char* smem, int k_begin, int k_end, int group) {
+  constexpr int LPW = PA::SPW + PB::SPW;
+  const uint32_t lds0 = lds_addr_of(smem);
+  const int nk = (k_end - k_begin + C::BK - 1) / C::BK;
 #pragma unroll
-  for (int t = 0; t < kTA; ++t)
+  for (int s = 0; s < C::NS - 1; ++s) {
+    pa.issue(lds0 + s * C::kStage, k_begin + s * C::BK);
+    pb.issue(lds0 + s * C::kStage + C::kPanelA, k_begin + s * C::BK);
+  }
+  wait_vmcnt<(C::NS - 2) * LPW>();
+  __builtin_amdgcn_s_barrier();
+  if (group == 1) __builtin_amdgcn_s_barrier();
+  int cur = 0;
+  for (int kt = 0; kt < nk; ++kt) {
+    // ---- memory phase
+    {
+      int nxt = cur + C::NS - 1; if (nxt >= C::NS) nxt -= C::NS;
+      const int k0 = k_begin + (kt + C::NS - 1) * C::BK;
+      pa.issue(lds0 + nxt * C::kStage, k0);
+      pb.issue(lds0 + nxt * C::kStage + C::kPanelA, k0);
+    }
+    const char* a_panel = smem + cur * C::kStage;
+    const char* b_panel = a_panel + C::kPanelA;
+    bf16x8 a[C::kKK][C::TA], b[C::kKK][C::TB];
 #pragma unroll
-    for (int u = 0; u < kTB; ++u)
+    for (int kk = 0; kk < C::kKK; ++kk) {
+#pragma unroll
+      for (int t = 0; t < C::TA; ++t) a[kk][t] = pa.frag(a_panel, t, kk);
+#pragma unroll
+      for (int u = 0; u < C::TB; ++u) b[kk][u] = pb.frag(b_panel, u, kk);
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    if (group == 1) wait_vmcnt<(C::NS - 2) * LPW>();   // group 1 reaches the barrier that opens stage kt+1 right after this phase
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- compute phase
+    __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+    for (int kk = 0; kk < C::kKK; ++kk)
+#pragma unroll
+      for (int t = 0; t < C::TA; ++t)
+#pragma unroll
+        for (int u = 0; u < C::TB; ++u)
+          acc[t][u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk][t], b[kk][u], acc[t][u], 0, 0, 0);
+    __builtin_amdgcn_s_setprio(0);
+    if (group == 0) wait_vmcnt<(C::NS - 2) * LPW>();   // group 0 opens stage kt+1 right after this phase
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    cur = cur + 1 == C::NS ? 0 : cur + 1;
+  }
+  if (group == 0) __builtin_amdgcn_s_barrier();
+  wait_vmcnt<0>();
+  __syncthreads();
+}
+
+template <int TA, int TB>
+__device__ __forceinline__ void zero_acc(f32x16 (&acc)[TA][TB]) {
+#pragma unroll
+  for (int t = 0; t < TA; ++t)
+#pragma unroll
+    for (int u = 0; u < TB; ++u)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[t][u][r] = 0.f;
 }

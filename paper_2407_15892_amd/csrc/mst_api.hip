@@ -152,7 +152,7 @@ mst_status run_forward_chunks(const Plan& p, const __bf16* H, const __bf16* W, c
     }
     {
       Scope sc(st, MST_K_LSE_FINALIZE);
-      hipLaunchKernelGGL(k_lse_finalize, dim3((rows + 255) / 256), dim3(256), 0, st,
+      hipLaunchKernelGGL(k_lse_finalize, dim3((rows + kFinRows - 1) / kFinRows), dim3(kFinRows * kFinGroups), 0, st,
                          part, p.C, p.n_vt, tgt, labels + r0, rows, (int)p.V, ignore_index,
                          lse ? lse + r0 : nullptr, nll ? nll + r0 : nullptr);
     }
@@ -279,7 +279,8 @@ mst_status mst_lmhead_ce_bwd(const void* H, const void* W, const int32_t* labels
     {
       Scope sc(st, MST_K_BWD_GEMM_DW);
       hipLaunchKernelGGL(k_bwd_gemm_dw, dim3(xcd_grid(p.n_vt * p.n_jt)), dim3(kThreads), kLdsBytes, st,
-                         G, p.ldg, Hc, rows, (int)p.d, (int)p.V, p.n_vt, p.n_jt, ctl, i > 0 ? 1 : 0, dW);
+                         G, p.ldg, Hc, rows, (int)p.d, (int)p.V, p.n_vt, p.n_jt, ctl, i > 0 ? 1 : 0,
+                         i == p.n_chunks - 1 ? 1 : 0, dW);
     }
   }
   return check_launch();

@@ -20,6 +20,15 @@
 
 namespace mst {
 
+// tile configuration of all four GEMMs: 2 x 4 waves, 4 x 2 MFMA tiles per wave, K step 64, 2 LDS stages
+typedef Cfg<2, 4, 4, 2, 64, 2> Tile;
+constexpr int kTile = 256;             // Tile::EA == Tile::EB
+constexpr int kBK = Tile::BK;
+constexpr int kThreads = Tile::kThreads;
+constexpr int kLdsBytes = Tile::kLds;
+constexpr int kTA = Tile::TA, kTB = Tile::TB;
+static_assert(Tile::EA == kTile && Tile::EB == kTile, "square 256 x 256 block tile");
+
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kMasked = -1.0e30f;     // stands for -infinity in max / sum-exp without producing NaN
@@ -95,12 +104,12 @@ __global__ __launch_bounds__(kThreads) void k_fwd_gemm_lse(
   const int wa = wave >> 2, wb = wave & 3;
 
   f32x16 acc[kTA][kTB];
-  zero_acc(acc);
-  PanelKC<kTA, true> pa;
-  PanelKC<kTB, false> pb;
+  zero_acc<kTA, kTB>(acc);
+  PanelKC<Tile, kTile, kTA, true> pa;
+  PanelKC<Tile, kTile, kTB, false> pb;
   pa.init(W + (size_t)v0 * d, d, V - v0, d, wave, lane, wa);
   pb.init(Hc + (size_t)s0 * d, d, rows - s0, d, wave, lane, wb);
-  gemm_mainloop(acc, pa, pb, smem, 0, d);
+  gemm_mainloop_pp<Tile>(acc, pa, pb, smem, 0, d, wa);
 
   const int va = v0 + wa * 128 + 16 * (lane >> 5);   // first vocabulary index of this lane in MFMA tile 0
   if (v0 + kTile > V) {                              // ragged last vocabulary tile: mask entries >= V
@@ -169,16 +178,32 @@ __global__ __launch_bounds__(kThreads) void k_fwd_gemm_lse(
   }
 }
 
-// per row: combine the vocab-tile partials in tile order; lse, nll
-__global__ __launch_bounds__(256) void k_lse_finalize(
+// per row: combine the vocab-tile partials into lse and nll.  A workgroup owns 64 rows; its 16
+// waves each fold every 16th vocabulary tile in ascending order, then the 16 partial results are
+// folded in wave order: the combination order is fixed, so lse is reproducible bit for bit.
+constexpr int kFinRows = 64;
+constexpr int kFinGroups = 16;
+__global__ __launch_bounds__(kFinRows * kFinGroups) void k_lse_finalize(
     const float2* __restrict__ part, int part_stride, int n_vt, const float* __restrict__ tgt,
     const int* __restrict__ labels_c, int rows, int V, int ignore_index,
     float* __restrict__ lse_c, float* __restrict__ nll_c) {
-  const int s = blockIdx.x * 256 + threadIdx.x;
-  if (s >= rows) return;
+  __shared__ float2 sh[kFinGroups][kFinRows];
+  const int r = threadIdx.x & (kFinRows - 1), g = threadIdx.x / kFinRows;
+  const int s = blockIdx.x * kFinRows + r;
   float m = kMasked, l = 0.f;
-  for (int vt = 0; vt < n_vt; ++vt) {
-    const float2 p = part[(size_t)vt * part_stride + s];
+  if (s < rows) {
+    for (int vt = g; vt < n_vt; vt += kFinGroups) {
+      const float2 p = part[(size_t)vt * part_stride + s];
+      const float mm = fmaxf(m, p.x);
+      l = l * fast_exp2((m - mm) * kLog2e) + p.y * fast_exp2((p.x - mm) * kLog2e);
+      m = mm;
+    }
+  }
+  sh[g][r] = make_float2(m, l);
+  __syncthreads();
+  if (g != 0 || s >= rows) return;
+  for (int q = 1; q < kFinGroups; ++q) {
+    const float2 p = sh[q][r];
     const float mm = fmaxf(m, p.x);
     l = l * fast_exp2((m - mm) * kLog2e) + p.y * fast_exp2((p.x - mm) * kLog2e);
     m = mm;
@@ -233,12 +258,12 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dlogits(
   const int wa = wave >> 2, wb = wave & 3;
 
   f32x16 acc[kTA][kTB];
-  zero_acc(acc);
-  PanelKC<kTA, true> pa;
-  PanelKC<kTB, false> pb;
+  zero_acc<kTA, kTB>(acc);
+  PanelKC<Tile, kTile, kTA, true> pa;
+  PanelKC<Tile, kTile, kTB, false> pb;
   pa.init(W + (size_t)v0 * d, d, V - v0, d, wave, lane, wa);
   pb.init(Hc + (size_t)s0 * d, d, rows - s0, d, wave, lane, wb);
-  gemm_mainloop(acc, pa, pb, smem, 0, d);
+  gemm_mainloop_pp<Tile>(acc, pa, pb, smem, 0, d, wa);
 
   const int va = v0 + wa * 128 + 16 * (lane >> 5);
 #pragma unroll
@@ -291,12 +316,12 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dh(
   if (k_end > V) k_end = V;
 
   f32x16 acc[kTA][kTB];
-  zero_acc(acc);
-  PanelKC<kTA, false> pa;
-  PanelKS<kTB> pb;
+  zero_acc<kTA, kTB>(acc);
+  PanelKC<Tile, kTile, kTA, false> pa;
+  PanelKS<Tile, kTile, kTB> pb;
   pa.init(G + (size_t)s0 * ldg, ldg, rows - s0, ldg, wave, lane, wa);
   pb.init(W + j0, d, V, d - j0, wave, lane, wb);
-  gemm_mainloop(acc, pa, pb, smem, k_begin, k_end);
+  gemm_mainloop_pp<Tile>(acc, pa, pb, smem, k_begin, k_end, wa);
 
   const float gamma = ctl->gamma;
 #pragma unroll
@@ -339,12 +364,16 @@ __global__ __launch_bounds__(256) void k_bwd_dh_reduce(const float* __restrict__
 // ---------------------------------------------------------------------------
 // backward 3: dW (+)= G^T H_chunk, contraction over the chunk's rows
 //   A side = vocabulary (G columns, K-strided), B side = hidden index j (H columns, K-strided)
-//   dW is fp32 and is its own accumulator: chunk 0 writes, later chunks read-modify-write,
-//   always in chunk order on one stream, so the sum order is fixed.
+//   dW is fp32 and is its own accumulator.  For every chunk after the first the old dW tile is
+//   loaded straight into the MFMA accumulators before the main loop (the loads fly while the
+//   first operand panels arrive), the chunk's products are accumulated on top, and the tile is
+//   stored once: one read and one write of dW per chunk and no extra registers.  The running
+//   sum is kept unscaled; the last chunk multiplies by grad_loss / N_valid.  Chunks run in
+//   order on one stream, so the summation order is fixed and dW is reproducible bit for bit.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dw(
     const __bf16* __restrict__ G, int ldg, const __bf16* __restrict__ Hc, int rows, int d, int V,
-    int n_vt, int n_jt, const Control* __restrict__ ctl, int accumulate, float* __restrict__ dW) {
+    int n_vt, int n_jt, const Control* __restrict__ ctl, int accumulate, int last, float* __restrict__ dW) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int w = xcd_work_item(n_vt * n_jt);
   if (w < 0) return;
@@ -355,14 +384,28 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dw(
   const int wa = wave >> 2, wb = wave & 3;
 
   f32x16 acc[kTA][kTB];
-  zero_acc(acc);
-  PanelKS<kTA> pa;
-  PanelKS<kTB> pb;
+  if (accumulate) {
+#pragma unroll
+    for (int t = 0; t < kTA; ++t)
+#pragma unroll
+      for (int u = 0; u < kTB; ++u) {
+        const int j = j0 + wb * 64 + 32 * u + (lane & 31);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int v = v0 + wa * 128 + 32 * t + a_index_in_tile<false>(r, lane);
+          acc[t][u][r] = (v < V && j < d) ? dW[(size_t)v * d + j] : 0.f;
+        }
+      }
+  } else {
+    zero_acc<kTA, kTB>(acc);
+  }
+  PanelKS<Tile, kTile, kTA> pa;
+  PanelKS<Tile, kTile, kTB> pb;
   pa.init(G + v0, ldg, rows, ldg - v0, wave, lane, wa);
   pb.init(Hc + j0, d, rows, d - j0, wave, lane, wb);
-  gemm_mainloop(acc, pa, pb, smem, 0, rows);
+  gemm_mainloop_pp<Tile>(acc, pa, pb, smem, 0, rows, wa);
 
-  const float gamma = ctl->gamma;
+  const float scale = last ? ctl->gamma : 1.0f;
 #pragma unroll
   for (int t = 0; t < kTA; ++t)
 #pragma unroll
@@ -371,11 +414,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dw(
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int v = v0 + wa * 128 + 32 * t + a_index_in_tile<false>(r, lane);
-        if (v < V && j < d) {
-          float* p = dW + (size_t)v * d + j;
-          const float x = gamma * acc[t][u][r];
-          *p = accumulate ? *p + x : x;
-        }
+        if (v < V && j < d) dW[(size_t)v * d + j] = scale * acc[t][u][r];
       }
     }
 }
