@@ -1,0 +1,91 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol the header declares, and
+its host-only logic (workspace sizing, chunk arithmetic limits, argument validation) behaves.
+No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import mst_inputs as mi
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def mst():
+    import paper_2407_15892_amd as m
+    if not os.path.exists(m.binding.LIB_PATH):
+        from paper_2407_15892_amd.build import build
+        build()
+    m.load_library()
+    return m
+
+
+def test_every_declared_symbol_is_exported(mst):
+    text = open(os.path.join(ROOT, "include", "mst_lmhead.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(mst_[a-z_]+)\s*\(", text))
+    assert {"mst_lmhead_ce_fwd", "mst_lmhead_ce_bwd", "mst_workspace_bytes", "mst_strerror"} <= names
+    lib = mst.load_library()
+    for n in sorted(names):
+        assert hasattr(lib, n), f"{n} is declared in the header but not exported"
+    assert "gfx950" in mst.mst_version()
+
+
+def test_workspace_stays_below_one_fp32_logits_chunk(mst):
+    for cfg in mi.CONFIGS.values():
+        f, b = mst.mst_workspace_bytes(cfg.S, cfg.d, cfg.V, cfg.M)
+        cap = cfg.C * cfg.V * 4
+        assert 0 < f <= cap and 0 < b <= cap, (cfg.name, f, b, cap)
+        # never a function of the full S x V logits
+        assert b < cfg.S * cfg.V * 2 or cfg.M == 1
+
+
+def test_workspace_scales_with_chunk_not_with_sequence(mst):
+    _, b1 = mst.mst_workspace_bytes(8192, 4096, 128256, 8)
+    _, b2 = mst.mst_workspace_bytes(32768, 4096, 128256, 32)   # same chunk length, 4x the sequence
+    assert b1 == b2
+    _, b3 = mst.mst_workspace_bytes(8192, 4096, 128256, 16)    # half the chunk
+    assert b3 < 0.7 * b1
+
+
+def test_shape_and_m_validation(mst):
+    st = mst.binding.mst_workspace_bytes_status
+    assert st(8, 16, 32, 1) == 0
+    assert st(0, 16, 32, 1) == -2
+    assert st(8, 0, 32, 1) == -2
+    assert st(8, 16, 0, 1) == -2
+    assert st(8, 12, 32, 1) == -2          # d % 8 != 0
+    assert st(8, 16, 32, 0) == -3
+    assert st(8, 16, 32, 9) == -3          # M > S
+    assert st(8, 1 << 16, 1 << 16, 1) == -2   # V * d >= 2^31
+    assert st(1 << 20, 8, 1 << 15, 1) == -2   # one chunk's dlogits >= 2^31 elements
+    for code in (0, -1, -2, -3, -4, -5, -6, -7):
+        assert isinstance(mst.mst_strerror(code), str) and mst.mst_strerror(code)
+
+
+def test_null_and_workspace_errors_come_before_any_launch(mst):
+    lib = mst.load_library()
+    S, d, V, M = 64, 16, 40, 2
+    f, b = mst.mst_workspace_bytes(S, d, V, M)
+    fake = 0x1000   # never dereferenced: validation fails first
+    # NULL H
+    assert lib.mst_lmhead_ce_fwd(None, fake, fake, S, d, V, -100, M, fake, f, fake, None, None, None) == -1
+    # NULL loss
+    assert lib.mst_lmhead_ce_fwd(fake, fake, fake, S, d, V, -100, M, fake, f, None, None, None, None) == -1
+    # workspace too small / NULL
+    assert lib.mst_lmhead_ce_fwd(fake, fake, fake, S, d, V, -100, M, fake, f - 1, fake, None, None, None) == -4
+    assert lib.mst_lmhead_ce_fwd(fake, fake, fake, S, d, V, -100, M, None, f, fake, None, None, None) == -4
+    # misaligned H
+    assert lib.mst_lmhead_ce_fwd(fake + 2, fake, fake, S, d, V, -100, M, fake, f, fake, None, None, None) == -5
+    # backward: NULL dW, small workspace (with and without lse)
+    assert lib.mst_lmhead_ce_bwd(fake, fake, fake, S, d, V, -100, M, 1.0, fake, fake, b, fake, None, None) == -1
+    assert lib.mst_lmhead_ce_bwd(fake, fake, fake, S, d, V, -100, M, 1.0, fake, fake, b - 1, fake, fake, None) == -4
+    assert lib.mst_lmhead_ce_bwd(fake, fake, fake, S, d, V, -100, M, 1.0, None, fake, b, fake, fake, None) == -4
+
+
+def test_profile_kind_names(mst):
+    lib = mst.load_library()
+    names = [lib.mst_profile_kind_name(i).decode() for i in range(mst.binding.PROFILE_KINDS)]
+    assert names[1] == "fwd_gemm_lse" and names[-1] == "bwd_gemm_dw" and len(set(names)) == len(names)
