@@ -96,7 +96,7 @@ def main() -> int:
 
     def step():
         mst.mst_lmhead_ce_fwd(H, W, labels, inp.ignore_index, M, ws, loss, lse, nv, stream)
-        mst.mst_lmhead_ce_bwd(H, W, labels, inp.ignore_index, M, 1.0, lse, ws, dH, dW, stream)
+        mst.mst_lmhead_ce_bwd(H, W, labels, inp.ignore_index, M, 1.0, lse, nv, ws, dH, dW, stream)
 
     for _ in range(args.warmup):
         step()
@@ -107,7 +107,7 @@ def main() -> int:
     e[0].record(stream)
     mst.mst_lmhead_ce_fwd(H, W, labels, inp.ignore_index, M, ws, loss, lse, nv, stream)
     e[1].record(stream)
-    mst.mst_lmhead_ce_bwd(H, W, labels, inp.ignore_index, M, 1.0, lse, ws, dH, dW, stream)
+    mst.mst_lmhead_ce_bwd(H, W, labels, inp.ignore_index, M, 1.0, lse, nv, ws, dH, dW, stream)
     e[2].record(stream)
     torch.cuda.synchronize()
     fwd_ms, bwd_ms = e[0].elapsed_time(e[1]), e[1].elapsed_time(e[2])

@@ -46,9 +46,10 @@
  *     aligned; workspace 256-byte aligned; 1 <= M <= S; V * d < 2^31;
  *     ceil(S/M) * (V rounded up to 8) < 2^31.
  *   - Arithmetic: bf16 operands, fp32 MFMA accumulation, fp32 log-sum-exp and
- *     softmax, dlogits rounded to bf16 (nearest even) before the two gradient
- *     GEMMs, dH rounded to bf16, dW fp32.  dW is accumulated chunk by chunk in
- *     a fixed order without atomics: repeated calls give bit-identical dW.
+ *     softmax, grad_loss / N_valid * dlogits rounded to bf16 (nearest even)
+ *     before the two gradient GEMMs, dH rounded to bf16, dW fp32.  dW is
+ *     accumulated over pairs of chunks in a fixed order without atomics:
+ *     repeated calls give bit-identical dW.
  *   - N_valid == 0: loss = 0, dH = 0, dW = 0.
  */
 #ifndef MST_LMHEAD_H
@@ -83,11 +84,12 @@ const char* mst_version(void);
 /*
  * Workspace sizes in bytes for the forward and the backward call (host-only,
  * launches nothing).  Either output pointer may be NULL.  The backward figure
- * is for the case `lse` is supplied; without it the backward call first runs
- * the forward's log-sum-exp pass and needs bwd_bytes + fwd_bytes + 4 * S
- * rounded up to a multiple of 256.
- * For the paper-shaped configurations both are below ceil(S/M) * V * 4 bytes,
- * the size of one chunk of fp32 logits.
+ * is for the case that `lse` and `n_valid` from the forward call are supplied:
+ * two bf16 dlogits chunks, 2 * ceil(S/M) * (V rounded up to 8) * 2 bytes, which
+ * for V % 8 == 0 is exactly one chunk of fp32 logits, ceil(S/M) * V * 4.
+ * Without `n_valid` the backward call counts the valid labels itself and needs
+ * 512 bytes more; without `lse` it also runs the forward's log-sum-exp pass
+ * first and needs bwd_bytes + 512 + fwd_bytes + 4 * S rounded up to 256.
  */
 mst_status mst_workspace_bytes(int64_t S, int64_t d, int64_t V, int32_t M,
                                size_t* fwd_bytes, size_t* bwd_bytes);
@@ -114,13 +116,15 @@ mst_status mst_lmhead_ce_fwd(const void* H, const void* W, const int32_t* labels
  * Backward: mini-sequence LM-head gradients with recomputation (Algorithm 4).
  *   grad_loss  upstream d(objective)/d(loss) (the algorithm's "nabla loss"), host value
  *   lse        optional fp32 [S] from the forward call (NULL: recomputed here)
+ *   n_valid    optional int64 scalar from the forward call on the same labels and
+ *              ignore_index (NULL: recounted here); it is trusted, not re-checked
  *   dH         out, bf16 [S, d], fully overwritten (ignored rows are exactly 0)
  *   dW         out, fp32 [V, d], fully overwritten
  */
 mst_status mst_lmhead_ce_bwd(const void* H, const void* W, const int32_t* labels,
                              int64_t S, int64_t d, int64_t V,
                              int32_t ignore_index, int32_t M,
-                             float grad_loss, const float* lse,
+                             float grad_loss, const float* lse, const int64_t* n_valid,
                              void* workspace, size_t workspace_bytes,
                              void* dH, float* dW,
                              void* stream);

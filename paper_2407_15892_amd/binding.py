@@ -57,7 +57,7 @@ def load_library() -> ctypes.CDLL:
                                       c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
     lib.mst_lmhead_ce_bwd.restype = c.c_int
     lib.mst_lmhead_ce_bwd.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int64, c.c_int64,
-                                      c.c_int32, c.c_int32, c.c_float, c.c_void_p,
+                                      c.c_int32, c.c_int32, c.c_float, c.c_void_p, c.c_void_p,
                                       c.c_void_p, c.c_size_t, c.c_void_p, c.c_void_p, c.c_void_p]
     lib.mst_profile_enable.restype = c.c_int
     lib.mst_profile_enable.argtypes = [c.c_int]
@@ -117,13 +117,14 @@ def mst_lmhead_ce_fwd(H, W, labels, ignore_index: int, M: int, workspace, loss, 
         _ptr(loss), _ptr(lse), _ptr(n_valid), _stream_handle(stream)))
 
 
-def mst_lmhead_ce_bwd(H, W, labels, ignore_index: int, M: int, grad_loss: float, lse, workspace, dH, dW,
+def mst_lmhead_ce_bwd(H, W, labels, ignore_index: int, M: int, grad_loss: float, lse, n_valid, workspace, dH, dW,
                       stream=None) -> None:
-    """Enqueue the backward pass.  dH bf16 [S,d] and dW fp32 [V,d] are fully overwritten."""
+    """Enqueue the backward pass.  lse fp32 [S] and n_valid int64 [1] come from the forward call (either may
+    be None).  dH bf16 [S,d] and dW fp32 [V,d] are fully overwritten."""
     S, d = H.shape
     V = W.shape[0]
     _check(load_library().mst_lmhead_ce_bwd(
-        _ptr(H), _ptr(W), _ptr(labels), S, d, V, ignore_index, M, float(grad_loss), _ptr(lse),
+        _ptr(H), _ptr(W), _ptr(labels), S, d, V, ignore_index, M, float(grad_loss), _ptr(lse), _ptr(n_valid),
         _ptr(workspace), workspace.numel() * workspace.element_size(),
         _ptr(dH), _ptr(dW), _stream_handle(stream)))
 

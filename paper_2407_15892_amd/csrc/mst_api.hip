@@ -30,8 +30,13 @@ struct Plan {
   int dh_ksteps;    // K steps (of kBK) per split
   // forward workspace (byte offsets)
   size_t f_nll, f_tgt, f_part, f_total;
-  // backward workspace
-  size_t b_g, b_partial, b_total;
+  // backward workspace: two dlogits slots of one chunk each (bf16), contiguous
+  size_t b_slot;      // bytes of one slot = C * ldg * 2
+  size_t b_total;     // 2 * b_slot: what the call needs when lse and n_valid are supplied
+  size_t b_ctl;       // offset of the control block used when n_valid is not supplied (aligned, after the slots)
+  size_t b_lse;       // offset of the lse scratch used when lse is not supplied
+  size_t b_fwd;       // offset of the forward region used when lse is not supplied
+  size_t b_total_max; // bytes needed when neither lse nor n_valid is supplied
 };
 
 mst_status make_plan(int64_t S, int64_t d, int64_t V, int32_t M, Plan* p) {
@@ -41,7 +46,7 @@ mst_status make_plan(int64_t S, int64_t d, int64_t V, int32_t M, Plan* p) {
   if (V * d >= (int64_t(1) << 31)) return MST_ERR_BAD_SHAPE;
   const int64_t C = (S + M - 1) / M;
   const int64_t ldg = (V + 7) / 8 * 8;
-  if (C * ldg >= (int64_t(1) << 31) || C * d >= (int64_t(1) << 31)) return MST_ERR_BAD_SHAPE;
+  if (C * ldg >= (int64_t(1) << 30) || C * d >= (int64_t(1) << 30)) return MST_ERR_BAD_SHAPE;
   p->S = S; p->d = d; p->V = V; p->M = M;
   p->C = (int)C;
   p->n_chunks = (int)((S + C - 1) / C);
@@ -56,10 +61,9 @@ mst_status make_plan(int64_t S, int64_t d, int64_t V, int32_t M, Plan* p) {
   if (split < 1) split = 1;
   if (split > kMaxDhSplit) split = kMaxDhSplit;
   if (split > ksteps) split = ksteps;
-  // keep dlogits + split partials inside the byte size of one fp32 logits chunk (C * V * 4)
+  // the split partials of one chunk live in the dlogits slot that is free at that moment
   {
-    const int64_t cap = C * V * 4, g_bytes = C * ldg * 2, per_split = C * d * 4;
-    const int64_t room = (cap - g_bytes - 1024) / per_split;
+    const int64_t room = (C * ldg * 2) / (C * d * 4);
     if (split > 1 && (int64_t)split > room) split = room >= 2 ? (int)room : 1;
   }
   p->dh_ksteps = (ksteps + split - 1) / split;
@@ -71,10 +75,12 @@ mst_status make_plan(int64_t S, int64_t d, int64_t V, int32_t M, Plan* p) {
   p->f_part = off; off = align_up(off + (size_t)p->n_vt * C * 8, 256);
   p->f_total = off;
 
-  off = sizeof(Control);
-  p->b_g = off;       off = align_up(off + (size_t)C * ldg * 2, 256);
-  p->b_partial = off; off = align_up(off + (p->dh_split > 1 ? (size_t)p->dh_split * C * d * 4 : 0), 256);
-  p->b_total = off;
+  p->b_slot = (size_t)C * ldg * 2;
+  p->b_total = 2 * p->b_slot;
+  p->b_ctl = align_up(p->b_total, 256);
+  p->b_lse = p->b_ctl + sizeof(Control);
+  p->b_fwd = p->b_lse + align_up((size_t)S * 4, 256);
+  p->b_total_max = p->b_fwd + p->f_total;
   return MST_OK;
 }
 
@@ -207,7 +213,7 @@ mst_status mst_lmhead_ce_fwd(const void* H, const void* W, const int32_t* labels
   float* nll = reinterpret_cast<float*>(ws + p.f_nll);
   {
     Scope sc(st, MST_K_LABEL_SCAN);
-    hipLaunchKernelGGL(k_label_scan, dim3(1), dim3(1024), 0, st, labels, (long long)S, (int)V, ignore_index, 1.0f, ctl);
+    hipLaunchKernelGGL(k_label_scan, dim3(1), dim3(1024), 0, st, labels, (long long)S, (int)V, ignore_index, ctl);
   }
   s = run_forward_chunks(p, static_cast<const __bf16*>(H), static_cast<const __bf16*>(W), labels, ignore_index,
                          ws, lse, nll, st);
@@ -222,65 +228,85 @@ mst_status mst_lmhead_ce_fwd(const void* H, const void* W, const int32_t* labels
 
 mst_status mst_lmhead_ce_bwd(const void* H, const void* W, const int32_t* labels, int64_t S, int64_t d, int64_t V,
                              int32_t ignore_index, int32_t M, float grad_loss, const float* lse,
-                             void* workspace, size_t workspace_bytes, void* dH, float* dW, void* stream) {
+                             const int64_t* n_valid, void* workspace, size_t workspace_bytes,
+                             void* dH, float* dW, void* stream) {
   Plan p;
   mst_status s = make_plan(S, d, V, M, &p);
   if (s != MST_OK) return s;
   if (!H || !W || !labels || !dH || !dW) return MST_ERR_NULL_POINTER;
-  const size_t need = lse ? p.b_total : p.b_total + p.f_total + align_up((size_t)S * 4, 256);
+  const size_t need = !lse ? p.b_total_max : (!n_valid ? p.b_lse : p.b_total);
   if (!workspace || workspace_bytes < need) return MST_ERR_WORKSPACE;
   if (misaligned(H, 16) || misaligned(W, 16) || misaligned(dH, 16) || misaligned(workspace, 256) ||
-      misaligned(lse, 4) || misaligned(dW, 4) || misaligned(labels, 4))
+      misaligned(lse, 4) || misaligned(dW, 4) || misaligned(labels, 4) || misaligned(n_valid, 8))
     return MST_ERR_ALIGNMENT;
   if ((s = prepare_device()) != MST_OK) return s;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   char* ws = static_cast<char*>(workspace);
-  Control* ctl = reinterpret_cast<Control*>(ws);
   const __bf16* Hb = static_cast<const __bf16*>(H);
   const __bf16* Wb = static_cast<const __bf16*>(W);
-  {
+  const long long* nv = reinterpret_cast<const long long*>(n_valid);
+  if (!nv) {
+    Control* ctl = reinterpret_cast<Control*>(ws + p.b_ctl);
     Scope sc(st, MST_K_LABEL_SCAN);
-    hipLaunchKernelGGL(k_label_scan, dim3(1), dim3(1024), 0, st, labels, (long long)S, (int)V, ignore_index, grad_loss, ctl);
+    hipLaunchKernelGGL(k_label_scan, dim3(1), dim3(1024), 0, st, labels, (long long)S, (int)V, ignore_index, ctl);
+    nv = &ctl->n_valid;
   }
   if (!lse) {
     // no saved log-sum-exp: run the forward's pass first, in the tail of the workspace
-    // (layout: [backward region | lse of S floats | forward region with its own unused control block])
-    float* lse_tmp = reinterpret_cast<float*>(ws + p.b_total);
-    char* fws = ws + p.b_total + align_up((size_t)S * 4, 256);
-    s = run_forward_chunks(p, Hb, Wb, labels, ignore_index, fws, lse_tmp, nullptr, st);
+    float* lse_tmp = reinterpret_cast<float*>(ws + p.b_lse);
+    s = run_forward_chunks(p, Hb, Wb, labels, ignore_index, ws + p.b_fwd, lse_tmp, nullptr, st);
     if (s != MST_OK) return s;
     lse = lse_tmp;
   }
-  __bf16* G = reinterpret_cast<__bf16*>(ws + p.b_g);
-  float* partial = reinterpret_cast<float*>(ws + p.b_partial);
+  __bf16* slot[2] = {reinterpret_cast<__bf16*>(ws), reinterpret_cast<__bf16*>(ws + p.b_slot)};
   __bf16* dHb = static_cast<__bf16*>(dH);
-  for (int i = 0; i < p.n_chunks; ++i) {
+
+  auto rows_of = [&](int i) { const int64_t r0 = (int64_t)i * p.C; return (int)((p.S - r0) < p.C ? (p.S - r0) : p.C); };
+  auto dlogits = [&](int i, __bf16* G) {
     const int64_t r0 = (int64_t)i * p.C;
-    const int rows = (int)((p.S - r0) < p.C ? (p.S - r0) : p.C);
-    const int n_st = (rows + kTile - 1) / kTile;
-    const __bf16* Hc = Hb + r0 * p.d;
-    {
-      Scope sc(st, MST_K_BWD_GEMM_DLOGITS);
-      hipLaunchKernelGGL(k_bwd_gemm_dlogits, dim3(xcd_grid(n_st * p.n_vt)), dim3(kThreads), kLdsBytes, st,
-                         Hc, Wb, labels + r0, lse + r0, rows, (int)p.d, (int)p.V, ignore_index, n_st, p.n_vt, G, p.ldg);
-    }
+    const int rows = rows_of(i), n_st = (rows + kTile - 1) / kTile;
+    Scope sc(st, MST_K_BWD_GEMM_DLOGITS);
+    hipLaunchKernelGGL(k_bwd_gemm_dlogits, dim3(xcd_grid(n_st * p.n_vt)), dim3(kThreads), kLdsBytes, st,
+                       Hb + r0 * p.d, Wb, labels + r0, lse + r0, rows, (int)p.d, (int)p.V, ignore_index, n_st, p.n_vt,
+                       nv, grad_loss, G, p.ldg);
+  };
+  auto grad_h = [&](int i, const __bf16* G, void* partial_space) {
+    const int64_t r0 = (int64_t)i * p.C;
+    const int rows = rows_of(i), n_st = (rows + kTile - 1) / kTile;
+    float* partial = static_cast<float*>(partial_space);
     {
       Scope sc(st, MST_K_BWD_GEMM_DH);
       hipLaunchKernelGGL(k_bwd_gemm_dh, dim3(xcd_grid(n_st * p.n_jt * p.dh_split)), dim3(kThreads), kLdsBytes, st,
-                         G, p.ldg, Wb, rows, (int)p.d, (int)p.V, n_st, p.n_jt, p.dh_split, p.dh_ksteps, ctl,
+                         G, p.ldg, Wb, rows, (int)p.d, (int)p.V, n_st, p.n_jt, p.dh_split, p.dh_ksteps,
                          partial, p.C, dHb + r0 * p.d);
     }
     if (p.dh_split > 1) {
       Scope sc(st, MST_K_BWD_DH_REDUCE);
       const size_t n = (size_t)rows * p.d;
       hipLaunchKernelGGL(k_bwd_dh_reduce, dim3((unsigned)((n / 8 + 255) / 256)), dim3(256), 0, st,
-                         partial, p.dh_split, (size_t)p.C * p.d, n, ctl, dHb + r0 * p.d);
+                         partial, p.dh_split, (size_t)p.C * p.d, n, dHb + r0 * p.d);
     }
-    {
-      Scope sc(st, MST_K_BWD_GEMM_DW);
-      hipLaunchKernelGGL(k_bwd_gemm_dw, dim3(xcd_grid(p.n_vt * p.n_jt)), dim3(kThreads), kLdsBytes, st,
-                         G, p.ldg, Hc, rows, (int)p.d, (int)p.V, p.n_vt, p.n_jt, ctl, i > 0 ? 1 : 0,
-                         i == p.n_chunks - 1 ? 1 : 0, dW);
+  };
+  auto grad_w = [&](int i_first, int rows, int accumulate) {
+    const int64_t r0 = (int64_t)i_first * p.C;
+    Scope sc(st, MST_K_BWD_GEMM_DW);
+    hipLaunchKernelGGL(k_bwd_gemm_dw, dim3(xcd_grid(p.n_vt * p.n_jt)), dim3(kThreads), kLdsBytes, st,
+                       slot[0], p.ldg, Hb + r0 * p.d, rows, (int)p.d, (int)p.V, p.n_vt, p.n_jt, accumulate, dW);
+  };
+
+  // Algorithm 4's loop over mini-sequences, two at a time: the chunk pair (A, B) shares one dW pass.
+  //   dlogits(A) -> slot 0 | dH(A), partials in slot 1 | dlogits(B) -> slot 1 | dW += [G_A; G_B]^T [H_A; H_B]
+  //   | dH(B), partials in slot 0
+  for (int ia = 0; ia < p.n_chunks; ia += 2) {
+    const int ib = ia + 1;
+    dlogits(ia, slot[0]);
+    grad_h(ia, slot[0], slot[1]);
+    if (ib < p.n_chunks) {
+      dlogits(ib, slot[1]);
+      grad_w(ia, p.C + rows_of(ib), ia > 0 ? 1 : 0);
+      grad_h(ib, slot[1], slot[0]);
+    } else {
+      grad_w(ia, rows_of(ia), ia > 0 ? 1 : 0);
     }
   }
   return check_launch();

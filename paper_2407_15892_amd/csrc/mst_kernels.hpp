@@ -34,16 +34,21 @@ constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kMasked = -1.0e30f;     // stands for -infinity in max / sum-exp without producing NaN
 constexpr int kNumXcd = 8;
 
-// Control block at the start of the workspace, written by k_label_scan.
+// Control block in the workspace, written by k_label_scan (n_valid is its first member).
 struct Control {
   long long n_valid;    // rows whose label is neither ignored nor out of range
   int bad_labels;       // rows whose label is outside [0, V) and not the ignore value
-  float gamma;          // grad_loss / n_valid (0 when n_valid == 0)
-  float pad[60];
+  int pad[61];
 };
 static_assert(sizeof(Control) == 256, "control block is one 256-byte line");
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// gamma = grad_loss / N_valid (Algorithm 4 lines 9-10 and the mean of the loss), 0 when nothing is valid
+__device__ __forceinline__ float gamma_of(const long long* __restrict__ n_valid, float grad_loss) {
+  const long long nv = *n_valid;
+  return nv > 0 ? (float)((double)grad_loss / (double)nv) : 0.f;
+}
 
 // XCD-aware remap of the linear workgroup id to a work item; returns -1 for padding workgroups.
 __device__ __forceinline__ int xcd_work_item(int total) {
@@ -55,10 +60,10 @@ __device__ __forceinline__ int xcd_work_item(int total) {
 inline int xcd_grid(int total) { return kNumXcd * ((total + kNumXcd - 1) / kNumXcd); }
 
 // ---------------------------------------------------------------------------
-// label scan: N_valid, range check, gamma.  One workgroup, integer sums only.
+// label scan: N_valid and range check.  One workgroup, integer sums only.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void k_label_scan(const int* __restrict__ labels, long long S, int V,
-                                                     int ignore_index, float grad_loss, Control* ctl) {
+                                                     int ignore_index, Control* ctl) {
   __shared__ long long s_valid[16];
   __shared__ int s_bad[16];
   long long nv = 0;
@@ -80,7 +85,6 @@ __global__ __launch_bounds__(1024) void k_label_scan(const int* __restrict__ lab
     for (int i = 0; i < 16; ++i) { tv += s_valid[i]; tb += s_bad[i]; }
     ctl->n_valid = tv;
     ctl->bad_labels = tb;
-    ctl->gamma = tv > 0 ? (float)((double)grad_loss / (double)tv) : 0.f;
   }
 }
 
@@ -241,13 +245,13 @@ __global__ __launch_bounds__(1024) void k_loss_reduce(const float* __restrict__ 
 }
 
 // ---------------------------------------------------------------------------
-// backward 1: recompute the logits tile, write softmax - onehot as bf16
-//   (the factor grad_loss / N_valid is applied in fp32 by the two gradient GEMMs)
+// backward 1: recompute the logits tile, write gamma * (softmax - onehot) as bf16
+//   (scaling by the single fp32 factor gamma before rounding only shifts the exponent; it costs no mantissa)
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dlogits(
     const __bf16* __restrict__ Hc, const __bf16* __restrict__ W, const int* __restrict__ labels_c,
     const float* __restrict__ lse_c, int rows, int d, int V, int ignore_index, int n_st, int n_vt,
-    __bf16* __restrict__ G, int ldg) {
+    const long long* __restrict__ n_valid, float grad_loss, __bf16* __restrict__ G, int ldg) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int w = xcd_work_item(n_st * n_vt);
   if (w < 0) return;
@@ -266,6 +270,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dlogits(
   gemm_mainloop_pp<Tile>(acc, pa, pb, smem, 0, d, wa);
 
   const int va = v0 + wa * 128 + 16 * (lane >> 5);
+  const float gamma = gamma_of(n_valid, grad_loss);
 #pragma unroll
   for (int u = 0; u < kTB; ++u) {
     const int s_local = s0 + wb * 64 + 32 * u + (lane & 31);
@@ -283,6 +288,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dlogits(
         const int v = vb + r;
         float g = fast_exp2(acc[t][u][r] * kLog2e - lb);
         if (v == y) g -= 1.0f;
+        g *= gamma;
         if (!valid || v >= V) g = 0.f;
         if (r < 8) lo[r] = (__bf16)g; else hi[r - 8] = (__bf16)g;
       }
@@ -298,7 +304,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dlogits(
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dh(
     const __bf16* __restrict__ G, int ldg, const __bf16* __restrict__ W, int rows, int d, int V,
-    int n_st, int n_jt, int n_split, int ksteps_per_split, const Control* __restrict__ ctl,
+    int n_st, int n_jt, int n_split, int ksteps_per_split,
     float* __restrict__ partial /* [n_split][rows_stride][d], used when n_split > 1 */, int rows_stride,
     __bf16* __restrict__ dHc /* used when n_split == 1 */) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -323,7 +329,6 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dh(
   pb.init(W + j0, d, V, d - j0, wave, lane, wb);
   gemm_mainloop_pp<Tile>(acc, pa, pb, smem, k_begin, k_end, wa);
 
-  const float gamma = ctl->gamma;
 #pragma unroll
   for (int t = 0; t < kTA; ++t)
 #pragma unroll
@@ -334,19 +339,18 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dh(
         const int s_local = s0 + wa * 128 + 32 * t + a_index_in_tile<false>(r, lane);
         if (s_local < rows && j < d) {
           if (n_split > 1) partial[((size_t)sp * rows_stride + s_local) * d + j] = acc[t][u][r];
-          else dHc[(size_t)s_local * d + j] = (__bf16)(gamma * acc[t][u][r]);
+          else dHc[(size_t)s_local * d + j] = (__bf16)acc[t][u][r];
         }
       }
     }
 }
 
-// fixed-order sum over the splits, scale, round to bf16.  8 outputs per thread.
+// fixed-order sum over the splits, round to bf16.  8 outputs per thread.
 __global__ __launch_bounds__(256) void k_bwd_dh_reduce(const float* __restrict__ partial, int n_split,
                                                        size_t split_stride /* rows_stride * d */, size_t n /* rows * d */,
-                                                       const Control* __restrict__ ctl, __bf16* __restrict__ dHc) {
+                                                       __bf16* __restrict__ dHc) {
   const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 8;
   if (i >= n) return;
-  const float gamma = ctl->gamma;
   float4 a0 = *reinterpret_cast<const float4*>(partial + i);
   float4 a1 = *reinterpret_cast<const float4*>(partial + i + 4);
   for (int sp = 1; sp < n_split; ++sp) {
@@ -356,24 +360,25 @@ __global__ __launch_bounds__(256) void k_bwd_dh_reduce(const float* __restrict__
     a1.x += b1.x; a1.y += b1.y; a1.z += b1.z; a1.w += b1.w;
   }
   bf16x8 o;
-  o[0] = (__bf16)(gamma * a0.x); o[1] = (__bf16)(gamma * a0.y); o[2] = (__bf16)(gamma * a0.z); o[3] = (__bf16)(gamma * a0.w);
-  o[4] = (__bf16)(gamma * a1.x); o[5] = (__bf16)(gamma * a1.y); o[6] = (__bf16)(gamma * a1.z); o[7] = (__bf16)(gamma * a1.w);
+  o[0] = (__bf16)a0.x; o[1] = (__bf16)a0.y; o[2] = (__bf16)a0.z; o[3] = (__bf16)a0.w;
+  o[4] = (__bf16)a1.x; o[5] = (__bf16)a1.y; o[6] = (__bf16)a1.z; o[7] = (__bf16)a1.w;
   *reinterpret_cast<bf16x8*>(dHc + i) = o;
 }
 
 // ---------------------------------------------------------------------------
-// backward 3: dW (+)= G^T H_chunk, contraction over the chunk's rows
+// backward 3: dW (+)= G^T H over the rows of one or two consecutive chunks
 //   A side = vocabulary (G columns, K-strided), B side = hidden index j (H columns, K-strided)
-//   dW is fp32 and is its own accumulator.  For every chunk after the first the old dW tile is
+//   dW is fp32 and is its own accumulator.  For every pass after the first the old dW tile is
 //   loaded straight into the MFMA accumulators before the main loop (the loads fly while the
-//   first operand panels arrive), the chunk's products are accumulated on top, and the tile is
-//   stored once: one read and one write of dW per chunk and no extra registers.  The running
-//   sum is kept unscaled; the last chunk multiplies by grad_loss / N_valid.  Chunks run in
-//   order on one stream, so the summation order is fixed and dW is reproducible bit for bit.
+//   first operand panels arrive), the products are accumulated on top, and the tile is stored
+//   once: one read and one write of dW per pass and no extra registers.  Because dlogits is
+//   kept as bf16, two chunks fit where one chunk of fp32 logits would, so a pass covers two
+//   chunks and dW is read and written half as often as there are chunks.  Passes run in order
+//   on one stream, so the summation order is fixed and dW is reproducible bit for bit.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dw(
     const __bf16* __restrict__ G, int ldg, const __bf16* __restrict__ Hc, int rows, int d, int V,
-    int n_vt, int n_jt, const Control* __restrict__ ctl, int accumulate, int last, float* __restrict__ dW) {
+    int n_vt, int n_jt, int accumulate, float* __restrict__ dW) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int w = xcd_work_item(n_vt * n_jt);
   if (w < 0) return;
@@ -405,7 +410,6 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dw(
   pb.init(Hc + j0, d, rows, d - j0, wave, lane, wb);
   gemm_mainloop_pp<Tile>(acc, pa, pb, smem, 0, rows, wa);
 
-  const float scale = last ? ctl->gamma : 1.0f;
 #pragma unroll
   for (int t = 0; t < kTA; ++t)
 #pragma unroll
@@ -414,7 +418,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dw(
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int v = v0 + wa * 128 + 32 * t + a_index_in_tile<false>(r, lane);
-        if (v < V && j < d) dW[(size_t)v * d + j] = scale * acc[t][u][r];
+        if (v < V && j < d) dW[(size_t)v * d + j] = acc[t][u][r];
       }
     }
 }

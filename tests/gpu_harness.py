@@ -49,17 +49,21 @@ class DeviceRun:
         t.cuda.synchronize()
         self.last_ws = ws
         self.lse = lse
+        self.nv = nv
         return float(loss.item()), (lse.cpu().numpy().astype(np.float64) if want_lse else None), int(nv.item())
 
-    def backward(self, grad_loss=1.0, use_lse=True, poison=True):
+    def backward(self, grad_loss=1.0, use_lse=True, use_nv=True, poison=True):
+        """use_lse / use_nv: hand the forward's lse / n_valid to the backward call (else it recomputes them)."""
         t = self.torch
+        nv = self.nv if use_nv else None
         if use_lse:
             assert self.lse is not None, "call forward(want_lse=True) first"
-            nbytes = self.bwd_bytes
+            nbytes = self.bwd_bytes if use_nv else self.bwd_bytes + 512
             lse = self.lse
         else:
-            nbytes = self.bwd_bytes + self.fwd_bytes + (self.S * 4 + 255) // 256 * 256
+            nbytes = self.bwd_bytes + 512 + self.fwd_bytes + (self.S * 4 + 255) // 256 * 256
             lse = None
+        self.bwd_bytes_used = nbytes
         ws = self._ws(nbytes)
         dH = t.empty((self.S, self.d), dtype=t.bfloat16, device="cuda")
         dW = t.empty((self.V, self.d), dtype=t.float32, device="cuda")
@@ -67,7 +71,7 @@ class DeviceRun:
             dH.view(t.int16).fill_(0x7FC0)   # NaN pattern: every element must be overwritten
             dW.fill_(float("nan"))
         self.mst.mst_lmhead_ce_bwd(self.H, self.W, self.labels, self.inp.ignore_index, self.M, grad_loss,
-                                   lse, ws[:nbytes], dH, dW)
+                                   lse, nv, ws[:nbytes], dH, dW)
         t.cuda.synchronize()
         self.last_ws = ws
         self.dH_t, self.dW_t = dH, dW

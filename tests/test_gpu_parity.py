@@ -19,7 +19,7 @@ def _harness():
     return DeviceRun, bf16_tensor_to_f64
 
 
-def _check_full(inp, M=None, grad_loss=1.0, use_lse=True):
+def _check_full(inp, M=None, grad_loss=1.0, use_lse=True, use_nv=True):
     DeviceRun, bf2f = _harness()
     ref = orc.lmhead_ce(inp.H_f64(), inp.W_f64(), inp.labels, inp.ignore_index, grad_loss=grad_loss)
     run = DeviceRun(inp, M=M)
@@ -30,7 +30,7 @@ def _check_full(inp, M=None, grad_loss=1.0, use_lse=True):
     else:
         assert loss == 0.0
     np.testing.assert_allclose(lse, ref["lse"], rtol=0, atol=2e-3 * max(1.0, np.abs(ref["lse"]).max()))
-    dH, dW = run.backward(grad_loss=grad_loss, use_lse=use_lse)
+    dH, dW = run.backward(grad_loss=grad_loss, use_lse=use_lse, use_nv=use_nv and use_lse)
     dH = bf2f(dH)
     dW = dW.cpu().numpy().astype(np.float64)
     assert np.isfinite(dH).all() and np.isfinite(dW).all()
@@ -53,6 +53,17 @@ def test_config1_tiny_matches_oracle():
 
 def test_config1_without_saved_lse_and_with_grad_loss():
     _check_full(mi.make_inputs(1), grad_loss=-0.75, use_lse=False)
+
+
+def test_config1_with_lse_but_recounted_n_valid():
+    _check_full(mi.make_inputs(1), grad_loss=2.0, use_lse=True, use_nv=False)
+
+
+@pytest.mark.parametrize("M", [3, 5])
+def test_odd_number_of_chunks_leaves_a_lone_last_chunk(M):
+    """The backward pairs chunks for the dW pass; an odd count ends with a single-chunk pass."""
+    cfg = mi.custom_config(650, 128, 900, M, index=310 + M, w_std=0.2)
+    _check_full(mi.make_inputs(cfg))
 
 
 @pytest.mark.parametrize("S,d,V,M", [
@@ -123,8 +134,9 @@ def test_out_of_range_label_is_reported_not_dereferenced():
     run = DeviceRun(inp)
     loss, lse, nv = run.forward()
     assert np.isnan(loss) and nv == -1
-    dH, dW = run.backward()          # must not fault; such rows are treated as ignored
+    dH, dW = run.backward(use_nv=False)   # must not fault; such rows are treated as ignored
     assert float(dH[5].float().abs().max()) == 0.0 and float(dH[9].float().abs().max()) == 0.0
+    assert float(dH[6].float().abs().max()) > 0.0
 
 
 def test_workspace_is_not_overrun():
@@ -135,7 +147,10 @@ def test_workspace_is_not_overrun():
     run.forward()
     assert bool((run.last_ws[run.fwd_bytes:] == 0xA5).all())
     run.backward()
+    assert run.bwd_bytes_used == run.bwd_bytes
     assert bool((run.last_ws[run.bwd_bytes:] == 0xA5).all())
+    run.backward(use_lse=False)
+    assert bool((run.last_ws[run.bwd_bytes_used:] == 0xA5).all())
 
 
 def test_argument_errors_are_synchronous():
