@@ -25,6 +25,15 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 
 GEMM_KINDS = ("fwd_gemm_lse", "bwd_gemm_dlogits", "bwd_gemm_dh", "bwd_gemm_dw")
 
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command (see profiles/),
+# scaled by what the same counters read for a device copy of known size; keyed by (config, kernel kind).
+PMC_TRAFFIC_BYTES = {
+    (2, "fwd_gemm_lse"): 1.824e9 + 0.004e9,
+    (2, "bwd_gemm_dlogits"): 1.831e9 + 0.270e9,
+    (2, "bwd_gemm_dh"): 1.579e9 + 0.067e9,
+    (2, "bwd_gemm_dw"): 4.944e9 + 2.101e9,
+}
+
 
 def cpu_baseline(inp, sample_rows: int):
     """The fp64 oracle as it stands, timed on the host cores on the first `sample_rows` tokens."""
@@ -56,10 +65,12 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2)
-    ap.add_argument("--cpu-sample-rows", type=int, default=384)
+    ap.add_argument("--cpu-sample-rows", type=int, default=4096)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="do not bracket kernels with events inside the timed region")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run one 1 GiB device-to-device copy, the known-size kernel the HBM counters are scaled by")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
@@ -98,6 +109,13 @@ def main() -> int:
         mst.mst_lmhead_ce_fwd(H, W, labels, inp.ignore_index, M, ws, loss, lse, nv, stream)
         mst.mst_lmhead_ce_bwd(H, W, labels, inp.ignore_index, M, 1.0, lse, nv, ws, dH, dW, stream)
 
+    if args.pmc_calibration:
+        a = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
+        b = torch.empty_like(a)
+        b.copy_(a)                       # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del a, b
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -134,18 +152,28 @@ def main() -> int:
         for k, (ms, n) in kern.items():
             if n:
                 kernels[k] = {"launches": n, "avg_ms": ms / n, "total_ms_per_step": ms / args.steps}
+        # every GEMM kind executes 2*S*d*V flop per step in total, split over its launches of that step
+        def flop_per_launch(kind):
+            return 2.0 * S * d * V / (kern[kind][1] / args.steps)
         dom = max(GEMM_KINDS, key=lambda k: kern[k][0])
         ms, n = kern[dom]
-        C = cfg.C
-        flop_per_launch = 2.0 * C * d * V           # one chunk's GEMM: C x d x V multiply-adds
-        achieved = flop_per_launch / (ms / n * 1e-3) / 1e12
+        achieved = flop_per_launch(dom) / (ms / n * 1e-3) / 1e12
+        traffic = PMC_TRAFFIC_BYTES.get((args.config, dom))
         roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
-                    "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
-                    "flop_per_launch": flop_per_launch, "avg_launch_ms": ms / n}
+                    "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
+                    "flop_per_launch": flop_per_launch(dom), "avg_launch_ms": ms / n,
+                    "launches_per_step": n / args.steps}
+        if dom == "bwd_gemm_dw":
+            # this kernel also moves dW through HBM once per launch (read + write, first launch write only)
+            passes = n / args.steps
+            alg_bytes = (2 * passes - 1) / passes * 4.0 * V * d + 2.0 * (S / passes) * V + 2.0 * (S / passes) * d
+            roofline["hbm_side"] = {"algorithmic_bytes_per_launch": alg_bytes,
+                                    "achieved_GBs": alg_bytes / (ms / n * 1e-3) / 1e9, "peak_GBs": PEAK_HBM_GBS,
+                                    "frac": alg_bytes / (ms / n * 1e-3) / 1e9 / PEAK_HBM_GBS}
         for k in GEMM_KINDS:
             ms_k, n_k = kern[k]
             if n_k:
-                kernels[k]["tflops"] = flop_per_launch / (ms_k / n_k * 1e-3) / 1e12
+                kernels[k]["tflops"] = flop_per_launch(k) / (ms_k / n_k * 1e-3) / 1e12
 
     out = {
         "metric": "LM-head+CE fwd+bwd TFLOP/s (8*S*d*V executed flop incl. recomputation)",

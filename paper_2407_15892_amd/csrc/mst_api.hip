@@ -290,7 +290,7 @@ mst_status mst_lmhead_ce_bwd(const void* H, const void* W, const int32_t* labels
   auto grad_w = [&](int i_first, int rows, int accumulate) {
     const int64_t r0 = (int64_t)i_first * p.C;
     Scope sc(st, MST_K_BWD_GEMM_DW);
-    hipLaunchKernelGGL(k_bwd_gemm_dw, dim3(xcd_grid(p.n_vt * p.n_jt)), dim3(kThreads), kLdsBytes, st,
+    hipLaunchKernelGGL(k_bwd_gemm_dw, dim3(xcd_grid_2d(p.n_vt, p.n_jt)), dim3(kThreads), kLdsBytes, st,
                        slot[0], p.ldg, Hb + r0 * p.d, rows, (int)p.d, (int)p.V, p.n_vt, p.n_jt, accumulate, dW);
   };
 

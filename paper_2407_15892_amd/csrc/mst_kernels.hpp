@@ -59,6 +59,33 @@ __device__ __forceinline__ int xcd_work_item(int total) {
 }
 inline int xcd_grid(int total) { return kNumXcd * ((total + kNumXcd - 1) / kNumXcd); }
 
+// Remap for a 2-D tile space (n_slow x n_fast) in which every tile reads one panel per coordinate:
+// each XCD owns a contiguous range of the slow coordinate and walks it in groups of kFastGroup fast
+// tiles, so that the 32 workgroups resident on an XCD form an 8 x 4 rectangle of tiles (12 distinct
+// panels for 32 workgroups) instead of a 2 x 16 strip (18 panels).  Returns false for padding workgroups.
+constexpr int kFastGroup = 4;
+__device__ __forceinline__ bool xcd_tile_2d(int n_slow, int n_fast, int* slow, int* fast) {
+  const int x = blockIdx.x % kNumXcd, q = blockIdx.x / kNumXcd;
+  const int spx = (n_slow + kNumXcd - 1) / kNumXcd;          // slow tiles per XCD
+  if (q >= spx * n_fast) return false;
+  const int full = n_fast / kFastGroup, rem = n_fast - full * kFastGroup;
+  const int per_full = spx * kFastGroup;
+  int sl, f;
+  if (q < full * per_full) {
+    const int g = q / per_full, r = q - g * per_full;
+    sl = r / kFastGroup;
+    f = g * kFastGroup + (r - sl * kFastGroup);
+  } else {
+    const int r = q - full * per_full;
+    sl = r / rem;
+    f = full * kFastGroup + (r - sl * rem);
+  }
+  *slow = x * spx + sl;
+  *fast = f;
+  return *slow < n_slow;
+}
+inline int xcd_grid_2d(int n_slow, int n_fast) { return kNumXcd * ((n_slow + kNumXcd - 1) / kNumXcd) * n_fast; }
+
 // ---------------------------------------------------------------------------
 // label scan: N_valid and range check.  One workgroup, integer sums only.
 // ---------------------------------------------------------------------------
@@ -380,9 +407,8 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dw(
     const __bf16* __restrict__ G, int ldg, const __bf16* __restrict__ Hc, int rows, int d, int V,
     int n_vt, int n_jt, int accumulate, float* __restrict__ dW) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  const int w = xcd_work_item(n_vt * n_jt);
-  if (w < 0) return;
-  const int vt = w / n_jt, jt = w - vt * n_jt;
+  int vt, jt;
+  if (!xcd_tile_2d(n_vt, n_jt, &vt, &jt)) return;
   const int v0 = vt * kTile, j0 = jt * kTile;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
