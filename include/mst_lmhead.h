@@ -95,6 +95,18 @@ mst_status mst_workspace_bytes(int64_t S, int64_t d, int64_t V, int32_t M,
                                size_t* fwd_bytes, size_t* bwd_bytes);
 
 /*
+ * Chunk-count policy (host-only).  Section 3.4 of the paper keeps a constant
+ * number of mini-sequences M = V / d for the LM head (32 for Llama3, 64 for
+ * Gemma-2 in its rounding) and notes that splitting a short sequence only costs
+ * time (its Appendix F measures an 11x slowdown at S = 1024, M = 32).  This
+ * returns V / d rounded to the nearest integer, then lowered so that a chunk
+ * never has fewer than 256 rows (one block tile of the GEMM kernels), and at
+ * least 1.  It is advice: every M with 1 <= M <= S is accepted by the calls.
+ * Returns 0 if S, d or V is not positive.
+ */
+int32_t mst_suggest_m(int64_t S, int64_t d, int64_t V);
+
+/*
  * Forward: mini-sequence LM-head loss (Algorithm 2).
  *   H        bf16 [S, d] row-major
  *   W        bf16 [V, d] row-major

@@ -7,6 +7,7 @@ from .binding import (  # noqa: F401
     mst_profile_collect,
     mst_profile_enable,
     mst_strerror,
+    mst_suggest_m,
     mst_version,
     mst_workspace_bytes,
 )

@@ -51,6 +51,8 @@ def load_library() -> ctypes.CDLL:
     lib.mst_workspace_bytes.restype = c.c_int
     lib.mst_workspace_bytes.argtypes = [c.c_int64, c.c_int64, c.c_int64, c.c_int32,
                                         c.POINTER(c.c_size_t), c.POINTER(c.c_size_t)]
+    lib.mst_suggest_m.restype = c.c_int32
+    lib.mst_suggest_m.argtypes = [c.c_int64, c.c_int64, c.c_int64]
     lib.mst_lmhead_ce_fwd.restype = c.c_int
     lib.mst_lmhead_ce_fwd.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int64, c.c_int64,
                                       c.c_int32, c.c_int32, c.c_void_p, c.c_size_t,
@@ -87,6 +89,11 @@ def mst_workspace_bytes(S: int, d: int, V: int, M: int):
     f, b = ctypes.c_size_t(0), ctypes.c_size_t(0)
     _check(load_library().mst_workspace_bytes(S, d, V, M, ctypes.byref(f), ctypes.byref(b)))
     return int(f.value), int(b.value)
+
+
+def mst_suggest_m(S: int, d: int, V: int) -> int:
+    """Chunk count advised by the paper's M = V / d rule, kept to chunks of at least 256 rows."""
+    return int(load_library().mst_suggest_m(S, d, V))
 
 
 def mst_workspace_bytes_status(S: int, d: int, V: int, M: int) -> int:

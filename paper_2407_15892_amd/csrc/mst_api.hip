@@ -186,6 +186,16 @@ const char* mst_strerror(mst_status s) {
 
 const char* mst_version(void) { return "mst-lmhead 0.1 (gfx950)"; }
 
+int32_t mst_suggest_m(int64_t S, int64_t d, int64_t V) {
+  if (S <= 0 || d <= 0 || V <= 0) return 0;
+  int64_t m = (2 * V + d) / (2 * d);             // V / d to the nearest integer
+  const int64_t by_rows = S / kTile;             // most chunks that still have one full block tile of rows
+  if (m > by_rows) m = by_rows;
+  if (m < 1) m = 1;
+  if (m > 0x7fffffff) m = 0x7fffffff;
+  return (int32_t)m;
+}
+
 mst_status mst_workspace_bytes(int64_t S, int64_t d, int64_t V, int32_t M, size_t* fwd_bytes, size_t* bwd_bytes) {
   Plan p;
   mst_status s = make_plan(S, d, V, M, &p);

@@ -91,3 +91,17 @@ def test_profile_kind_names(mst):
     lib = mst.load_library()
     names = [lib.mst_profile_kind_name(i).decode() for i in range(mst.binding.PROFILE_KINDS)]
     assert names[1] == "fwd_gemm_lse" and names[-1] == "bwd_gemm_dw" and len(set(names)) == len(names)
+
+
+def test_chunk_count_policy(mst):
+    """Section 3.4: M = V / d for the LM head; never chunks shorter than one 256-row tile."""
+    assert mst.mst_suggest_m(32768, 4096, 128256) == 31      # 31.3 -> 31 (the paper rounds this to 32)
+    assert mst.mst_suggest_m(131072, 3584, 256000) == 71     # 71.4 -> 71 (the paper quotes 64)
+    assert mst.mst_suggest_m(8192, 4096, 128256) == 31
+    assert mst.mst_suggest_m(1024, 4096, 128256) == 4        # the 11x-slowdown case: keep 256-row chunks
+    assert mst.mst_suggest_m(100, 4096, 128256) == 1         # short sequence: do not split
+    assert mst.mst_suggest_m(8192, 4096, 1000) == 1
+    assert mst.mst_suggest_m(0, 4096, 1000) == 0
+    for S, d, V in [(8192, 4096, 128256), (777, 264, 1000), (64, 8, 40)]:
+        M = mst.mst_suggest_m(S, d, V)
+        assert 1 <= M <= S and mst.binding.mst_workspace_bytes_status(S, d, V, M) == 0
