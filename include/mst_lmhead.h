@@ -46,10 +46,11 @@
  *     aligned; workspace 256-byte aligned; 1 <= M <= S; V * d < 2^31;
  *     ceil(S/M) * (V rounded up to 8) < 2^31.
  *   - Arithmetic: bf16 operands, fp32 MFMA accumulation, fp32 log-sum-exp and
- *     softmax, grad_loss / N_valid * dlogits rounded to bf16 (nearest even)
- *     before the two gradient GEMMs, dH rounded to bf16, dW fp32.  dW is
- *     accumulated over pairs of chunks in a fixed order without atomics:
- *     repeated calls give bit-identical dW.
+ *     softmax, dlogits = softmax - onehot rounded to bf16 (nearest even)
+ *     before the two gradient GEMMs, grad_loss / N_valid applied in fp32 by
+ *     their epilogues, dH rounded to bf16, dW fp32.  dW is accumulated over
+ *     pairs of chunks in a fixed order without atomics: repeated calls give
+ *     bit-identical dW.
  *   - N_valid == 0: loss = 0, dH = 0, dW = 0.
  */
 #ifndef MST_LMHEAD_H

@@ -278,7 +278,7 @@ mst_status mst_lmhead_ce_bwd(const void* H, const void* W, const int32_t* labels
     Scope sc(st, MST_K_BWD_GEMM_DLOGITS);
     hipLaunchKernelGGL(k_bwd_gemm_dlogits, dim3(xcd_grid(n_st * p.n_vt)), dim3(kThreads), kLdsBytes, st,
                        Hb + r0 * p.d, Wb, labels + r0, lse + r0, rows, (int)p.d, (int)p.V, ignore_index, n_st, p.n_vt,
-                       nv, grad_loss, G, p.ldg);
+                       G, p.ldg);
   };
   auto grad_h = [&](int i, const __bf16* G, void* partial_space) {
     const int64_t r0 = (int64_t)i * p.C;
@@ -288,20 +288,21 @@ mst_status mst_lmhead_ce_bwd(const void* H, const void* W, const int32_t* labels
       Scope sc(st, MST_K_BWD_GEMM_DH);
       hipLaunchKernelGGL(k_bwd_gemm_dh, dim3(xcd_grid(n_st * p.n_jt * p.dh_split)), dim3(kThreads), kLdsBytes, st,
                          G, p.ldg, Wb, rows, (int)p.d, (int)p.V, n_st, p.n_jt, p.dh_split, p.dh_ksteps,
-                         partial, p.C, dHb + r0 * p.d);
+                         nv, grad_loss, partial, p.C, dHb + r0 * p.d);
     }
     if (p.dh_split > 1) {
       Scope sc(st, MST_K_BWD_DH_REDUCE);
       const size_t n = (size_t)rows * p.d;
       hipLaunchKernelGGL(k_bwd_dh_reduce, dim3((unsigned)((n / 8 + 255) / 256)), dim3(256), 0, st,
-                         partial, p.dh_split, (size_t)p.C * p.d, n, dHb + r0 * p.d);
+                         partial, p.dh_split, (size_t)p.C * p.d, n, nv, grad_loss, dHb + r0 * p.d);
     }
   };
-  auto grad_w = [&](int i_first, int rows, int accumulate) {
+  auto grad_w = [&](int i_first, int i_last, int rows) {
     const int64_t r0 = (int64_t)i_first * p.C;
     Scope sc(st, MST_K_BWD_GEMM_DW);
     hipLaunchKernelGGL(k_bwd_gemm_dw, dim3(xcd_grid_2d(p.n_vt, p.n_jt)), dim3(kThreads), kLdsBytes, st,
-                       slot[0], p.ldg, Hb + r0 * p.d, rows, (int)p.d, (int)p.V, p.n_vt, p.n_jt, accumulate, dW);
+                       slot[0], p.ldg, Hb + r0 * p.d, rows, (int)p.d, (int)p.V, p.n_vt, p.n_jt,
+                       i_first > 0 ? 1 : 0, i_last == p.n_chunks - 1 ? 1 : 0, nv, grad_loss, dW);
   };
 
   // Algorithm 4's loop over mini-sequences, two at a time: the chunk pair (A, B) shares one dW pass.
@@ -313,10 +314,10 @@ mst_status mst_lmhead_ce_bwd(const void* H, const void* W, const int32_t* labels
     grad_h(ia, slot[0], slot[1]);
     if (ib < p.n_chunks) {
       dlogits(ib, slot[1]);
-      grad_w(ia, p.C + rows_of(ib), ia > 0 ? 1 : 0);
+      grad_w(ia, ib, p.C + rows_of(ib));
       grad_h(ib, slot[1], slot[0]);
     } else {
-      grad_w(ia, rows_of(ia), ia > 0 ? 1 : 0);
+      grad_w(ia, ia, rows_of(ia));
     }
   }
   return check_launch();

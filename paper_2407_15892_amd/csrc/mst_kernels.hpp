@@ -272,13 +272,14 @@ __global__ __launch_bounds__(1024) void k_loss_reduce(const float* __restrict__ 
 }
 
 // ---------------------------------------------------------------------------
-// backward 1: recompute the logits tile, write gamma * (softmax - onehot) as bf16
-//   (scaling by the single fp32 factor gamma before rounding only shifts the exponent; it costs no mantissa)
+// backward 1: recompute the logits tile, write softmax - onehot as bf16
+//   (kept unscaled so that the label entry p - 1 stays within 2^-9 of -1, its nearest bf16 neighbour in most
+//   rows; the factor gamma = grad_loss / N_valid is applied in fp32 by the two gradient GEMMs)
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dlogits(
     const __bf16* __restrict__ Hc, const __bf16* __restrict__ W, const int* __restrict__ labels_c,
     const float* __restrict__ lse_c, int rows, int d, int V, int ignore_index, int n_st, int n_vt,
-    const long long* __restrict__ n_valid, float grad_loss, __bf16* __restrict__ G, int ldg) {
+    __bf16* __restrict__ G, int ldg) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int w = xcd_work_item(n_st * n_vt);
   if (w < 0) return;
@@ -297,7 +298,6 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dlogits(
   gemm_mainloop_pp<Tile>(acc, pa, pb, smem, 0, d, wa);
 
   const int va = v0 + wa * 128 + 16 * (lane >> 5);
-  const float gamma = gamma_of(n_valid, grad_loss);
 #pragma unroll
   for (int u = 0; u < kTB; ++u) {
     const int s_local = s0 + wb * 64 + 32 * u + (lane & 31);
@@ -315,7 +315,6 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dlogits(
         const int v = vb + r;
         float g = fast_exp2(acc[t][u][r] * kLog2e - lb);
         if (v == y) g -= 1.0f;
-        g *= gamma;
         if (!valid || v >= V) g = 0.f;
         if (r < 8) lo[r] = (__bf16)g; else hi[r - 8] = (__bf16)g;
       }
@@ -332,6 +331,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dlogits(
 __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dh(
     const __bf16* __restrict__ G, int ldg, const __bf16* __restrict__ W, int rows, int d, int V,
     int n_st, int n_jt, int n_split, int ksteps_per_split,
+    const long long* __restrict__ n_valid, float grad_loss,
     float* __restrict__ partial /* [n_split][rows_stride][d], used when n_split > 1 */, int rows_stride,
     __bf16* __restrict__ dHc /* used when n_split == 1 */) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -366,18 +366,20 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dh(
         const int s_local = s0 + wa * 128 + 32 * t + a_index_in_tile<false>(r, lane);
         if (s_local < rows && j < d) {
           if (n_split > 1) partial[((size_t)sp * rows_stride + s_local) * d + j] = acc[t][u][r];
-          else dHc[(size_t)s_local * d + j] = (__bf16)acc[t][u][r];
+          else dHc[(size_t)s_local * d + j] = (__bf16)(gamma_of(n_valid, grad_loss) * acc[t][u][r]);
         }
       }
     }
 }
 
-// fixed-order sum over the splits, round to bf16.  8 outputs per thread.
+// fixed-order sum over the splits, scale by gamma, round to bf16.  8 outputs per thread.
 __global__ __launch_bounds__(256) void k_bwd_dh_reduce(const float* __restrict__ partial, int n_split,
                                                        size_t split_stride /* rows_stride * d */, size_t n /* rows * d */,
+                                                       const long long* __restrict__ n_valid, float grad_loss,
                                                        __bf16* __restrict__ dHc) {
   const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 8;
   if (i >= n) return;
+  const float gamma = gamma_of(n_valid, grad_loss);
   float4 a0 = *reinterpret_cast<const float4*>(partial + i);
   float4 a1 = *reinterpret_cast<const float4*>(partial + i + 4);
   for (int sp = 1; sp < n_split; ++sp) {
@@ -387,8 +389,8 @@ __global__ __launch_bounds__(256) void k_bwd_dh_reduce(const float* __restrict__
     a1.x += b1.x; a1.y += b1.y; a1.z += b1.z; a1.w += b1.w;
   }
   bf16x8 o;
-  o[0] = (__bf16)a0.x; o[1] = (__bf16)a0.y; o[2] = (__bf16)a0.z; o[3] = (__bf16)a0.w;
-  o[4] = (__bf16)a1.x; o[5] = (__bf16)a1.y; o[6] = (__bf16)a1.z; o[7] = (__bf16)a1.w;
+  o[0] = (__bf16)(gamma * a0.x); o[1] = (__bf16)(gamma * a0.y); o[2] = (__bf16)(gamma * a0.z); o[3] = (__bf16)(gamma * a0.w);
+  o[4] = (__bf16)(gamma * a1.x); o[5] = (__bf16)(gamma * a1.y); o[6] = (__bf16)(gamma * a1.z); o[7] = (__bf16)(gamma * a1.w);
   *reinterpret_cast<bf16x8*>(dHc + i) = o;
 }
 
@@ -400,12 +402,14 @@ __global__ __launch_bounds__(256) void k_bwd_dh_reduce(const float* __restrict__
 //   first operand panels arrive), the products are accumulated on top, and the tile is stored
 //   once: one read and one write of dW per pass and no extra registers.  Because dlogits is
 //   kept as bf16, two chunks fit where one chunk of fp32 logits would, so a pass covers two
-//   chunks and dW is read and written half as often as there are chunks.  Passes run in order
+//   chunks and dW is read and written half as often as there are chunks.  The running sum is
+//   kept unscaled; the last pass multiplies by gamma = grad_loss / N_valid.  Passes run in order
 //   on one stream, so the summation order is fixed and dW is reproducible bit for bit.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dw(
     const __bf16* __restrict__ G, int ldg, const __bf16* __restrict__ Hc, int rows, int d, int V,
-    int n_vt, int n_jt, int accumulate, float* __restrict__ dW) {
+    int n_vt, int n_jt, int accumulate, int last, const long long* __restrict__ n_valid, float grad_loss,
+    float* __restrict__ dW) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   int vt, jt;
   if (!xcd_tile_2d(n_vt, n_jt, &vt, &jt)) return;
@@ -436,6 +440,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dw(
   pb.init(Hc + j0, d, rows, d - j0, wave, lane, wb);
   gemm_mainloop_pp<Tile>(acc, pa, pb, smem, 0, rows, wa);
 
+  const float scale = last ? gamma_of(n_valid, grad_loss) : 1.0f;
 #pragma unroll
   for (int t = 0; t < kTA; ++t)
 #pragma unroll
@@ -444,7 +449,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dw(
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int v = v0 + wa * 128 + 32 * t + a_index_in_tile<false>(r, lane);
-        if (v < V && j < d) dW[(size_t)v * d + j] = acc[t][u][r];
+        if (v < V && j < d) dW[(size_t)v * d + j] = scale * acc[t][u][r];
       }
     }
 }
