@@ -173,3 +173,57 @@ def test_argument_errors_are_synchronous():
     with pytest.raises(mst.MstError) as e:
         mst.mst_lmhead_ce_fwd(H_misaligned, run.W, run.labels, -100, 2, ws, loss)
     assert e.value.status == -5
+
+
+def test_zero_upstream_gradient_gives_zero_gradients():
+    DeviceRun, _ = _harness()
+    inp = mi.make_inputs(mi.custom_config(300, 64, 700, 2, index=320))
+    run = DeviceRun(inp)
+    run.forward()
+    dH, dW = run.backward(grad_loss=0.0)
+    assert float(dH.float().abs().max()) == 0.0 and float(dW.abs().max()) == 0.0
+
+
+def test_ignore_value_inside_the_vocabulary_range():
+    """ignore_index = 0: rows labelled 0 are skipped, class 0 still takes part in every softmax."""
+    inp = mi.make_inputs(mi.custom_config(400, 64, 300, 3, index=321, ignore_frac=0.0))
+    inp.labels[::7] = 0
+    inp.ignore_index = 0
+    _check_full(inp)
+
+
+def test_labels_on_tile_boundaries():
+    """Labels at the first / last column of vocabulary tiles and of the 16-wide accumulator groups."""
+    inp = mi.make_inputs(mi.custom_config(512, 128, 1000, 2, index=322, ignore_frac=0.0))
+    special = np.array([0, 15, 16, 31, 32, 127, 128, 255, 256, 511, 512, 767, 768, 999], dtype=np.int32)
+    inp.labels[:] = special[np.arange(512) % len(special)]
+    _check_full(inp)
+
+
+def test_many_row_tiles_per_chunk():
+    """Long chunks (thousands of rows, dozens of row tiles) against a small head."""
+    cfg = mi.custom_config(20000, 64, 520, 3, index=323, w_std=0.3, label_dist="zipf")
+    _check_full(mi.make_inputs(cfg))
+
+
+def test_repeated_calls_reuse_the_same_buffers():
+    """Back-to-back calls on one stream with the same workspace (as bench.py does) stay correct."""
+    import torch
+    import paper_2407_15892_amd as mst
+    DeviceRun, bf2f = _harness()
+    inp = mi.make_inputs(mi.custom_config(700, 136, 900, 4, index=324, w_std=0.2))
+    ref = orc.lmhead_ce(inp.H_f64(), inp.W_f64(), inp.labels)
+    run = DeviceRun(inp)
+    ws = torch.empty(max(run.fwd_bytes, run.bwd_bytes), dtype=torch.uint8, device="cuda")
+    loss = torch.zeros(1, device="cuda")
+    lse = torch.empty(run.S, device="cuda")
+    nv = torch.zeros(1, dtype=torch.int64, device="cuda")
+    dH = torch.empty((run.S, run.d), dtype=torch.bfloat16, device="cuda")
+    dW = torch.empty((run.V, run.d), dtype=torch.float32, device="cuda")
+    for _ in range(3):
+        mst.mst_lmhead_ce_fwd(run.H, run.W, run.labels, -100, 4, ws, loss, lse, nv)
+        mst.mst_lmhead_ce_bwd(run.H, run.W, run.labels, -100, 4, 1.0, lse, nv, ws, dH, dW)
+    torch.cuda.synchronize()
+    assert abs(float(loss) - ref["loss"]) <= LOSS_RTOL * abs(ref["loss"])
+    assert np.abs(dW.cpu().numpy() - ref["dW"]).max() <= GRAD_TOL * np.abs(ref["dW"]).max()
+    assert np.abs(bf2f(dH) - ref["dH"]).max() <= GRAD_TOL * np.abs(ref["dH"]).max()
