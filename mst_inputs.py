@@ -1,4 +1,5 @@
-"""Seeded synthetic inputs for the mini-sequence LM-head + cross-entropy path.
+"""Seeded synthetic inputs for the mini-sequence LM-head + cross-entropy path
+and for the mini-sequence MLP path.
 
 This module is the only code shared by the CPU oracle's tests and the GPU
 harness.  It holds no arithmetic of the method itself: it draws hidden states
@@ -6,7 +7,9 @@ H, the output-embedding matrix W and the labels with the shapes and value
 distributions of the five benchmark configurations (Llama3-8B, Gemma-2 and
 Mistral-7B shaped LM heads; the shapes are the ones the paper's model listing
 and evaluation section name), rounds H and W to bfloat16 and hands them back
-as raw bit patterns plus exact float widenings.
+as raw bit patterns plus exact float widenings.  For the MLP block it draws
+the block input X, the three projection matrices and an upstream gradient dO
+with the Llama shapes of the paper's model listing.
 
 bfloat16 is carried as ``numpy.uint16`` bit patterns (numpy has no bf16 type).
 """
@@ -21,6 +24,7 @@ BASE_SEED = 20240715
 
 # tensor ids fed into the Philox key so every tensor has its own stream
 _T_H, _T_W, _T_LABEL, _T_IGNORE, _T_PERM = 1, 2, 3, 4, 5
+_T_X, _T_WG, _T_WU, _T_WD, _T_DO = 11, 12, 13, 14, 15
 
 
 # ----------------------------------------------------------------------------
@@ -166,3 +170,68 @@ def make_inputs(cfg) -> Inputs:
     H = _normal_bf16(_rng(cfg.seed, _T_H), cfg.S, cfg.d, cfg.h_std)
     W = _normal_bf16(_rng(cfg.seed, _T_W), cfg.V, cfg.d, cfg.w_std)
     return Inputs(cfg, H, W, make_labels(cfg))
+
+
+# ----------------------------------------------------------------------------
+# mini-sequence MLP (three bias-free linear layers and SiLU)
+# ----------------------------------------------------------------------------
+@dataclass(frozen=True)
+class MlpConfig:
+    name: str
+    index: int          # 1-based index among the MLP configurations
+    S: int              # tokens (batch folded into the sequence)
+    d: int              # hidden size
+    I: int              # intermediate size
+    M: int              # number of mini-sequences
+    x_std: float = 1.0      # block input (after the normalisation layer)
+    w_std: float = 0.02     # all three projections
+    do_std: float = 1.0     # upstream gradient of the block output
+
+    @property
+    def C(self) -> int:
+        return -(-self.S // self.M)
+
+    @property
+    def seed(self) -> int:
+        return BASE_SEED + 1000 + self.index
+
+
+# chunk size C = d (the constant chunk size the paper's chunk-based variant uses for MLP blocks)
+MLP_CONFIGS = {
+    1: MlpConfig("tiny", 1, 512, 256, 896, 2),
+    2: MlpConfig("llama3-8b-mlp", 2, 8192, 4096, 14336, 2),
+    3: MlpConfig("llama3-8b-mlp-long", 3, 32768, 4096, 14336, 8),
+    4: MlpConfig("llama2-7b-mlp", 4, 16384, 4096, 11008, 4),
+}
+
+
+def custom_mlp_config(S, d, I, M, *, index=100, x_std=1.0, w_std=0.02, do_std=1.0, name="custom") -> MlpConfig:
+    return MlpConfig(name, index, S, d, I, M, x_std, w_std, do_std)
+
+
+@dataclass
+class MlpInputs:
+    cfg: MlpConfig
+    X_bits: np.ndarray    # uint16 [S, d]
+    Wg_bits: np.ndarray   # uint16 [I, d]   gate projection, stored [out, in]
+    Wu_bits: np.ndarray   # uint16 [I, d]   up projection
+    Wd_bits: np.ndarray   # uint16 [d, I]   down projection
+    dO_bits: np.ndarray   # uint16 [S, d]   upstream gradient of the block output
+
+    def f64(self, name: str, rows=None) -> np.ndarray:
+        b = getattr(self, name + "_bits")
+        return bf16_bits_to_f64(b if rows is None else b[rows])
+
+
+def make_mlp_inputs(cfg) -> MlpInputs:
+    """Draw the tensors of an MLP configuration (an int 1..4 or an MlpConfig)."""
+    if not isinstance(cfg, MlpConfig):
+        cfg = MLP_CONFIGS[int(cfg)]
+    return MlpInputs(
+        cfg,
+        _normal_bf16(_rng(cfg.seed, _T_X), cfg.S, cfg.d, cfg.x_std),
+        _normal_bf16(_rng(cfg.seed, _T_WG), cfg.I, cfg.d, cfg.w_std),
+        _normal_bf16(_rng(cfg.seed, _T_WU), cfg.I, cfg.d, cfg.w_std),
+        _normal_bf16(_rng(cfg.seed, _T_WD), cfg.d, cfg.I, cfg.w_std),
+        _normal_bf16(_rng(cfg.seed, _T_DO), cfg.S, cfg.d, cfg.do_std),
+    )
