@@ -1,4 +1,4 @@
-"""Mini-sequence LM-head + cross-entropy for MI355X (gfx950): ctypes binding of the HIP library."""
+"""Mini-sequence LM-head + cross-entropy and mini-sequence MLP for MI355X (gfx950): ctypes bindings of the HIP libraries."""
 from .binding import (  # noqa: F401
     MstError,
     load_library,
@@ -10,4 +10,14 @@ from .binding import (  # noqa: F401
     mst_suggest_m,
     mst_version,
     mst_workspace_bytes,
+)
+from .mlp_binding import (  # noqa: F401
+    load_mlp_library,
+    mst_mlp_bwd,
+    mst_mlp_fwd,
+    mst_mlp_profile_collect,
+    mst_mlp_profile_enable,
+    mst_mlp_suggest_m,
+    mst_mlp_version,
+    mst_mlp_workspace_bytes,
 )

@@ -1,4 +1,4 @@
-"""Builds libmst_lmhead.so (HIP, gfx950) in-tree with hipcc."""
+"""Builds libmst_lmhead.so and libmst_mlp.so (HIP, gfx950) in-tree with hipcc."""
 from __future__ import annotations
 
 import os
@@ -8,6 +8,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libmst_lmhead.so")
+MLP_LIB_PATH = os.path.join(HERE, "libmst_mlp.so")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -23,10 +24,9 @@ def find_hipcc() -> str:
     raise RuntimeError("hipcc not found; a ROCm toolchain is required to build the library")
 
 
-def build(verbose: bool = False) -> str:
-    """Compile csrc/mst_api.hip into libmst_lmhead.so; returns the library path."""
-    src = os.path.join(CSRC, "mst_api.hip")
-    tmp = LIB_PATH + ".tmp"
+def _compile(src_name: str, lib_path: str, verbose: bool) -> str:
+    src = os.path.join(CSRC, src_name)
+    tmp = lib_path + ".tmp"
     cmd = [find_hipcc(), *HIPCC_FLAGS, "-o", tmp, src]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if verbose or res.returncode != 0:
@@ -35,8 +35,15 @@ def build(verbose: bool = False) -> str:
         print(res.stderr)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + res.stderr[-4000:])
-    os.replace(tmp, LIB_PATH)
-    return LIB_PATH
+    os.replace(tmp, lib_path)
+    return lib_path
+
+
+def build(verbose: bool = False) -> str:
+    """Compile csrc/mst_api.hip into libmst_lmhead.so and csrc/mst_mlp_api.hip into libmst_mlp.so;
+    returns the path of the LM-head library."""
+    _compile("mst_mlp_api.hip", MLP_LIB_PATH, verbose)
+    return _compile("mst_api.hip", LIB_PATH, verbose)
 
 
 if __name__ == "__main__":

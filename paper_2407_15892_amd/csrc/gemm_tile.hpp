@@ -53,6 +53,14 @@ struct Cfg {
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
 }
+// same, for a base address or size that the compiler cannot prove wave-uniform (it is, by construction):
+// the descriptor has to live in scalar registers
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc_uniform(const void* base, uint32_t bytes) {
+  const uint64_t a = reinterpret_cast<uint64_t>(base);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+  return make_rsrc(reinterpret_cast<const void*>(((uint64_t)hi << 32) | lo), __builtin_amdgcn_readfirstlane(bytes));
+}
 __device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t rsrc, uint32_t voffset, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                :: "s"(lds_addr), "v"(voffset), "s"(rsrc) : "memory");
@@ -104,6 +112,30 @@ struct PanelKC {
     for (int i = 0; i < SPW; ++i) {
       const uint32_t lrow = RPS * (slot0 + i) + rin;                                   // LDS row
       const uint32_t grow = (lrow & ~31u) + a_row_of_mfma_row<kPermute>(lrow & 31);    // global row
+      const int chunk = p ^ swz(lrow);
+      kelem[i] = chunk * 8;
+      voff[i] = grow * ld_bytes + chunk * 16;
+    }
+    const int row0 = wave_side_index * (32 * TILES) + (lane & 31);
+#pragma unroll
+    for (int kk = 0; kk < C::kKK; ++kk) rd[kk] = row0 * RB + (((2 * kk + (lane >> 5)) ^ swz(row0)) * 16);
+  }
+  // Variant for a panel whose 32-row MFMA tiles come from different matrices: every wave loads exactly one
+  // 32-row tile of the panel (SPW * RPS == 32), `tile_base` points at the first of this wave's 32 source
+  // rows and `rows_valid` (may be <= 0) says how many of them exist.  Reading is as in init().
+  __device__ __forceinline__ void init_tile32(const void* tile_base, uint32_t ld_elems, int rows_valid, uint32_t k_elems,
+                                              int wave, int lane, int wave_side_index) {
+    static_assert(SPW * RPS == 32, "one 32-row tile per wave");
+    const uint32_t ld_bytes = ld_elems * 2;
+    const uint32_t rows = rows_valid <= 0 ? 0u : (rows_valid < 32 ? (uint32_t)rows_valid : 32u);
+    rsrc = make_rsrc_uniform(tile_base, rows * ld_bytes);
+    k_limit = k_elems;
+    slot0 = wave * SPW;
+    const int rin = lane / CPR, p = lane % CPR;
+#pragma unroll
+    for (int i = 0; i < SPW; ++i) {
+      const uint32_t lrow = RPS * (slot0 + i) + rin;
+      const uint32_t grow = a_row_of_mfma_row<kPermute>(lrow & 31);
       const int chunk = p ^ swz(lrow);
       kelem[i] = chunk * 8;
       voff[i] = grow * ld_bytes + chunk * 16;

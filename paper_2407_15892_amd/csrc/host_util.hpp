@@ -1,0 +1,66 @@
+// Host-side helpers shared by the library sources: per-kernel event timing and small checks.
+// Each shared library that includes this header owns its own profiler instance.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <mutex>
+#include <vector>
+
+namespace mst_host {
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) != 0; }
+
+struct Profiler {
+  std::mutex mu;
+  bool enabled = false;
+  struct Rec { int kind; hipEvent_t a, b; };
+  std::vector<Rec> recs;
+  std::vector<hipEvent_t> pool;
+  hipEvent_t get() {
+    if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+  }
+  void enable(bool on) {
+    std::lock_guard<std::mutex> lk(mu);
+    enabled = on;
+  }
+  // adds elapsed ms / launch counts per kind, clears the record; false if an event could not be read
+  bool collect(int n_kinds, double* ms_per_kind, int64_t* launches_per_kind) {
+    std::lock_guard<std::mutex> lk(mu);
+    bool ok = true;
+    for (auto& r : recs) {
+      float ms = 0.f;
+      if (hipEventSynchronize(r.b) != hipSuccess || hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) ok = false;
+      if (r.kind >= 0 && r.kind < n_kinds) {
+        if (ms_per_kind) ms_per_kind[r.kind] += ms;
+        if (launches_per_kind) launches_per_kind[r.kind] += 1;
+      }
+      pool.push_back(r.a);
+      pool.push_back(r.b);
+    }
+    recs.clear();
+    return ok;
+  }
+};
+
+struct Scope {   // brackets one launch with events when profiling is on
+  Profiler& pr; hipStream_t st; int kind; hipEvent_t a = nullptr, b = nullptr; bool on;
+  Scope(Profiler& p, hipStream_t s, int k) : pr(p), st(s), kind(k), on(p.enabled) {
+    if (!on) return;
+    std::lock_guard<std::mutex> lk(pr.mu);
+    a = pr.get(); b = pr.get();
+    if (a) (void)hipEventRecord(a, st);
+  }
+  ~Scope() {
+    if (!on) return;
+    if (b) (void)hipEventRecord(b, st);
+    std::lock_guard<std::mutex> lk(pr.mu);
+    if (a && b) pr.recs.push_back({kind, a, b});
+  }
+};
+
+}  // namespace mst_host

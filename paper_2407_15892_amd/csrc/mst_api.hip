@@ -3,10 +3,10 @@
 // 1-3 and Algorithm 4 lines 1-4 of the paper: partition, then loop), workspace
 // carving, launches, and the optional per-kernel event timing.
 #include "../../include/mst_lmhead.h"
+#include "host_util.hpp"
 #include "mst_kernels.hpp"
 
 #include <mutex>
-#include <vector>
 
 namespace {
 
@@ -15,7 +15,8 @@ using namespace mst;
 constexpr int kNumCu = 256;          // MI355X compute units; only steers the dH split choice
 constexpr int kMaxDhSplit = 16;
 
-inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+using mst_host::align_up;
+using mst_host::misaligned;
 
 struct Plan {
   int64_t S, d, V;
@@ -85,35 +86,9 @@ mst_status make_plan(int64_t S, int64_t d, int64_t V, int32_t M, Plan* p) {
 }
 
 // ------------------------------------------------------------------ profiling
-struct Profiler {
-  std::mutex mu;
-  bool enabled = false;
-  struct Rec { int kind; hipEvent_t a, b; };
-  std::vector<Rec> recs;
-  std::vector<hipEvent_t> pool;
-  hipEvent_t get() {
-    if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
-    hipEvent_t e;
-    if (hipEventCreate(&e) != hipSuccess) return nullptr;
-    return e;
-  }
-};
-Profiler g_prof;
-
-struct Scope {   // brackets one launch with events when profiling is on
-  hipStream_t st; int kind; hipEvent_t a = nullptr, b = nullptr; bool on;
-  Scope(hipStream_t s, int k) : st(s), kind(k), on(g_prof.enabled) {
-    if (!on) return;
-    std::lock_guard<std::mutex> lk(g_prof.mu);
-    a = g_prof.get(); b = g_prof.get();
-    if (a) (void)hipEventRecord(a, st);
-  }
-  ~Scope() {
-    if (!on) return;
-    if (b) (void)hipEventRecord(b, st);
-    std::lock_guard<std::mutex> lk(g_prof.mu);
-    if (a && b) g_prof.recs.push_back({kind, a, b});
-  }
+mst_host::Profiler g_prof;
+struct Scope : mst_host::Scope {
+  Scope(hipStream_t s, int k) : mst_host::Scope(g_prof, s, k) {}
 };
 
 std::once_flag g_attr_once;
@@ -128,8 +103,6 @@ void set_kernel_attributes() {
   set((const void*)k_bwd_gemm_dh);
   set((const void*)k_bwd_gemm_dw);
 }
-
-bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) != 0; }
 
 mst_status check_launch() { return hipGetLastError() == hipSuccess ? MST_OK : MST_ERR_LAUNCH; }
 
@@ -324,26 +297,12 @@ mst_status mst_lmhead_ce_bwd(const void* H, const void* W, const int32_t* labels
 }
 
 mst_status mst_profile_enable(int enable) {
-  std::lock_guard<std::mutex> lk(g_prof.mu);
-  g_prof.enabled = enable != 0;
+  g_prof.enable(enable != 0);
   return MST_OK;
 }
 
 mst_status mst_profile_collect(double* ms_per_kind, int64_t* launches_per_kind) {
-  std::lock_guard<std::mutex> lk(g_prof.mu);
-  mst_status out = MST_OK;
-  for (auto& r : g_prof.recs) {
-    float ms = 0.f;
-    if (hipEventSynchronize(r.b) != hipSuccess || hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) out = MST_ERR_LAUNCH;
-    if (r.kind >= 0 && r.kind < MST_PROFILE_KINDS) {
-      if (ms_per_kind) ms_per_kind[r.kind] += ms;
-      if (launches_per_kind) launches_per_kind[r.kind] += 1;
-    }
-    g_prof.pool.push_back(r.a);
-    g_prof.pool.push_back(r.b);
-  }
-  g_prof.recs.clear();
-  return out;
+  return g_prof.collect(MST_PROFILE_KINDS, ms_per_kind, launches_per_kind) ? MST_OK : MST_ERR_LAUNCH;
 }
 
 const char* mst_profile_kind_name(int kind) {
