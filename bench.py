@@ -7,6 +7,9 @@ resident in HBM.  The workload is the Llama3-8B-shaped configuration
 (S=8192, d=4096, V=128256, M=8).  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--no-cpu-baseline]
+
+`--path mlp` times the mini-sequence MLP block instead (forward + backward with recomputation of the
+intermediates, Llama3-8B shape S=8192, d=4096, I=14336, chunk size C = d) and prints the same kind of line.
 """
 from __future__ import annotations
 
@@ -59,8 +62,133 @@ def cpu_baseline(inp, sample_rows: int):
     }
 
 
+MLP_KINDS = ("gateup", "down", "da", "gateup_bwd", "dx", "dw")
+# executed flop per step of each MLP kernel kind, in units of S*d*I
+MLP_FLOP_UNITS = {"gateup": 4.0, "down": 2.0, "da": 2.0, "gateup_bwd": 4.0, "dx": 4.0, "dw": 6.0}
+MLP_PMC_TRAFFIC_BYTES = {}
+
+
+def mlp_cpu_baseline(inp, sample_rows: int):
+    """The fp64 MLP oracle as it stands, timed on the host cores on the first `sample_rows` tokens."""
+    import numpy as np
+    from oracle import mlp_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    rows = np.arange(min(sample_rows, inp.cfg.S))
+    args = [inp.f64("X", rows), inp.f64("Wg"), inp.f64("Wu"), inp.f64("Wd"), inp.f64("dO", rows)]
+    t0 = time.perf_counter()
+    r = orc.mlp(*args)
+    dt = time.perf_counter() - t0
+    flops = 18.0 * len(rows) * inp.cfg.d * inp.cfg.I          # forward 6 + backward 12, no recomputation
+    return {
+        "value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+        "sample": f"first {len(rows)} of {inp.cfg.S} tokens of the same workload, full d and I, fp64 numpy "
+                  f"(O, dX and the three weight gradients = 18*S*d*I flop), {dt:.1f} s wall",
+        "seconds": dt, "checksum": float(np.abs(r["O"]).sum()),
+    }
+
+
+def main_mlp(args) -> int:
+    import torch
+    import mst_inputs as mi
+    import paper_2407_15892_amd as mst
+    from tests.gpu_harness import to_device_bf16
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 2
+    mst.load_mlp_library()
+    cfg = mi.MLP_CONFIGS[args.config]
+    t0 = time.perf_counter()
+    inp = mi.make_mlp_inputs(cfg)
+    gen_s = time.perf_counter() - t0
+    S, d, I, M = cfg.S, cfg.d, cfg.I, cfg.M
+    X, Wg, Wu, Wd, dO = (to_device_bf16(getattr(inp, n + "_bits")) for n in ("X", "Wg", "Wu", "Wd", "dO"))
+    fwd_bytes, bwd_bytes = mst.mst_mlp_workspace_bytes(S, d, I, M)
+    ws = torch.empty(max(fwd_bytes, bwd_bytes), dtype=torch.uint8, device="cuda")
+    O = torch.empty((S, d), dtype=torch.bfloat16, device="cuda")
+    dX = torch.empty((S, d), dtype=torch.bfloat16, device="cuda")
+    dWg = torch.empty((I, d), dtype=torch.float32, device="cuda")
+    dWu = torch.empty((I, d), dtype=torch.float32, device="cuda")
+    dWd = torch.empty((d, I), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def fwd():
+        mst.mst_mlp_fwd(X, Wg, Wu, Wd, M, ws, O, stream)
+
+    def bwd():
+        mst.mst_mlp_bwd(X, Wg, Wu, Wd, dO, M, ws, dX, dWg, dWu, dWd, stream)
+
+    if args.pmc_calibration:
+        a = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
+        b = torch.empty_like(a)
+        b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
+    for _ in range(args.warmup):
+        fwd(); bwd()
+    torch.cuda.synchronize()
+    e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    e[0].record(stream); fwd(); e[1].record(stream); bwd(); e[2].record(stream)
+    torch.cuda.synchronize()
+    fwd_ms, bwd_ms = e[0].elapsed_time(e[1]), e[1].elapsed_time(e[2])
+
+    timing = not args.no_kernel_timing
+    mst.mst_mlp_profile_enable(timing)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        fwd(); bwd()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    kern = mst.mst_mlp_profile_collect() if timing else {}
+    mst.mst_mlp_profile_enable(False)
+
+    ms_per_step = dt * 1e3 / args.steps
+    f_exec = 22.0 * S * d * I          # forward 6, recomputation 4, dA 2, dX 4, weight gradients 6
+    tflops = f_exec / (ms_per_step * 1e-3) / 1e12
+    roofline, kernels = None, {}
+    if kern:
+        for k, (ms, n) in kern.items():
+            if n:
+                fl = MLP_FLOP_UNITS[k] * S * d * I / (n / args.steps)
+                kernels[k] = {"launches": n, "avg_ms": ms / n, "total_ms_per_step": ms / args.steps,
+                              "tflops": fl / (ms / n * 1e-3) / 1e12}
+        dom = max(MLP_KINDS, key=lambda k: kern[k][0])
+        ms, n = kern[dom]
+        fl = MLP_FLOP_UNITS[dom] * S * d * I / (n / args.steps)
+        achieved = fl / (ms / n * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+                    "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+                    "traffic": MLP_PMC_TRAFFIC_BYTES.get((args.config, dom)),
+                    "flop_per_launch": fl, "avg_launch_ms": ms / n, "launches_per_step": n / args.steps}
+    out = {
+        "metric": "MsT-MLP fwd+bwd TFLOP/s (22*S*d*I executed flop incl. recomputation)",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"MLP config {cfg.index} {cfg.name}: S={S} d={d} I={I} M={M} (C={cfg.C}), bf16 X/weights/dO, "
+                               f"fwd+bwd with recomputation of the intermediates", "S": S, "d": d, "I": I, "M": M},
+        "frac_of_bf16_peak": tflops / PEAK_BF16_TFLOPS,
+        "tflops_18SdI_convention": 18.0 * S * d * I / (ms_per_step * 1e-3) / 1e12,
+        "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
+        "peak_workspace_bytes": {"fwd": fwd_bytes, "bwd": bwd_bytes, "full_sequence_intermediate_bf16": S * I * 2},
+        "checksum_O": float(O.float().abs().sum().item()),
+        "roofline": roofline, "kernels": kernels, "input_generation_s": gen_s,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = mlp_cpu_baseline(inp, args.cpu_sample_rows)
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
+    ap.add_argument("--path", choices=("lmhead", "mlp"), default="lmhead",
+                    help="which block to time: the LM-head + cross-entropy (the headline metric) or the MLP")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
@@ -76,6 +204,8 @@ def main() -> int:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
               file=sys.stderr)
         return 2
+    if args.path == "mlp":
+        return main_mlp(args)
 
     import numpy as np
     import torch

@@ -101,12 +101,13 @@ def mlp(X, Wg, Wu, Wd, dO) -> dict:
 
 
 def mlp_grads_sampled(X, Wg, Wu, Wd, dO, rows, inter_rows, hidden_rows) -> dict:
-    """Exact gradients on samples, for sizes where the full result is too slow:
-    dX[rows, :], dWg[inter_rows, :], dWu[inter_rows, :] and dWd[hidden_rows, :].
+    """Exact values on samples, for sizes where the full result is too slow:
+    O[rows, :], dX[rows, :], dWg[inter_rows, :], dWu[inter_rows, :] and the sub-block
+    dWd[hidden_rows][:, inter_rows].
 
-    dX of a token needs only that token's row of X and dO.  Row i of dWg / dWu
-    needs column i of dG / dU over all tokens, i.e. only rows i of Wg, Wu and
-    column i of Wd.  Row j of dWd needs column j of dO and the whole of A.
+    O and dX of a token need only that token's row of X and dO.  Row i of dWg / dWu needs column i of
+    dG / dU over all tokens, i.e. only rows i of Wg, Wu and column i of Wd.  Entry (j, i) of dWd needs
+    column j of dO and column i of A, which again needs only rows i of Wg and Wu.
     """
     X = np.asarray(X, dtype=np.float64)
     Wg = np.asarray(Wg, dtype=np.float64)
@@ -117,26 +118,21 @@ def mlp_grads_sampled(X, Wg, Wu, Wd, dO, rows, inter_rows, hidden_rows) -> dict:
     inter_rows = np.asarray(inter_rows, dtype=np.int64)
     hidden_rows = np.asarray(hidden_rows, dtype=np.int64)
     out = {}
-    # dX on sampled tokens
+    # O and dX on sampled tokens
     Xr, dOr = X[rows], dO[rows]
     G = Xr @ Wg.T
     U = Xr @ Wu.T
+    out["O"] = (silu(G) * U) @ Wd.T
     dA = dOr @ Wd
     out["dX"] = (dA * U * silu_grad(G)) @ Wg + (dA * silu(G)) @ Wu
-    # dWg, dWu on sampled intermediate indices
+    # dWg, dWu on sampled intermediate indices, over all tokens
     Gi = X @ Wg[inter_rows].T
     Ui = X @ Wu[inter_rows].T
     dAi = dO @ Wd[:, inter_rows]
     out["dWg"] = (dAi * Ui * silu_grad(Gi)).T @ X
     out["dWu"] = (dAi * silu(Gi)).T @ X
-    # dWd on sampled hidden indices: sum over tokens of dO[s, j] * A[s, :], A formed in row blocks
-    acc = np.zeros((len(hidden_rows), Wg.shape[0]), dtype=np.float64)
-    blk = max(1, (1 << 25) // max(Wg.shape[0], 1))
-    for r0 in range(0, X.shape[0], blk):
-        Xb = X[r0:r0 + blk]
-        Ab = silu(Xb @ Wg.T) * (Xb @ Wu.T)
-        acc += dO[r0:r0 + blk][:, hidden_rows].T @ Ab
-    out["dWd"] = acc
+    # dWd on sampled (hidden, intermediate) pairs
+    out["dWd"] = dO[:, hidden_rows].T @ (silu(Gi) * Ui)
     return out
 
 

@@ -177,10 +177,11 @@ def test_sampled_equals_full():
     r = orc.mlp(X, Wg, Wu, Wd, dO)
     rows, ir, hr = [0, 5, 19], [1, 11, 4], [6, 0]
     s = orc.mlp_grads_sampled(X, Wg, Wu, Wd, dO, rows, ir, hr)
+    assert np.allclose(s["O"], r["O"][rows], rtol=1e-13, atol=1e-13)
     assert np.allclose(s["dX"], r["dX"][rows], rtol=1e-13, atol=1e-13)
     assert np.allclose(s["dWg"], r["dWg"][ir], rtol=1e-13, atol=1e-13)
     assert np.allclose(s["dWu"], r["dWu"][ir], rtol=1e-13, atol=1e-13)
-    assert np.allclose(s["dWd"], r["dWd"][hr], rtol=1e-13, atol=1e-13)
+    assert np.allclose(s["dWd"], r["dWd"][hr][:, ir], rtol=1e-13, atol=1e-13)
 
 
 def test_shape_errors():
