@@ -65,7 +65,15 @@ def cpu_baseline(inp, sample_rows: int):
 MLP_KINDS = ("gateup", "down", "da", "gateup_bwd", "dx", "dw")
 # executed flop per step of each MLP kernel kind, in units of S*d*I
 MLP_FLOP_UNITS = {"gateup": 4.0, "down": 2.0, "da": 2.0, "gateup_bwd": 4.0, "dx": 4.0, "dw": 6.0}
-MLP_PMC_TRAFFIC_BYTES = {}
+# HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of `bench.py --path mlp` (see profiles/)
+MLP_PMC_TRAFFIC_BYTES = {
+    (2, "gateup"): 1.410e9 + 0.118e9,
+    (2, "down"): 0.705e9 + 0.035e9,
+    (2, "da"): 0.712e9 + 0.126e9,
+    (2, "gateup_bwd"): 1.534e9 + 0.473e9,
+    (2, "dx"): 1.412e9 + 0.036e9,
+    (2, "dw"): 1.069e9 + 0.235e9,
+}
 
 
 def mlp_cpu_baseline(inp, sample_rows: int):
