@@ -154,8 +154,11 @@ struct PanelKC {
   }
 };
 
-// K-strided panel [BK k][EXT index]
-template <class C, int EXT, int TILES>
+// K-strided panel [BK k][EXT index].  kPermute (A side only): MFMA row m of a 32-wide tile reads index
+// a_row_of_mfma_row(m), so that a lane's 16 accumulator registers hold 16 consecutive indices.  The
+// permutation keeps groups of 4 consecutive indices together, which is the granule one lane hands to the
+// transposing read, so it is applied in the read addresses and the panel in LDS stays in memory order.
+template <class C, int EXT, int TILES, bool kPermute = false>
 struct PanelKS {
   static constexpr int BK = C::BK;
   static constexpr int RB = EXT * 2;
@@ -187,7 +190,8 @@ struct PanelKS {
     const int g = lane >> 4, i16 = lane & 15;
 #pragma unroll
     for (int t = 0; t < TILES; ++t) {
-      const int col = wave_side_index * (32 * TILES) + 32 * t + 16 * (g & 1) + 4 * (i16 & 3);
+      const int m0 = 16 * (g & 1) + 4 * (i16 & 3);          // first of the 4 MFMA rows this lane's piece feeds
+      const int col = wave_side_index * (32 * TILES) + 32 * t + a_row_of_mfma_row<kPermute>(m0);
       const int krow = 8 * (g >> 1) + (i16 >> 2);
       rd[t] = krow * RB + (((col >> 3) ^ (2 * (i16 >> 2))) * 16) + (col & 7) * 2;
     }

@@ -22,6 +22,8 @@ namespace mst {
 
 // tile configuration of all four GEMMs: 2 x 4 waves, 4 x 2 MFMA tiles per wave, K step 64, 2 LDS stages
 typedef Cfg<2, 4, 4, 2, 64, 2> Tile;
+// same wave grid, half as wide on the B side: 256 x 128 block tile, wave tile 128 x 32
+typedef Cfg<2, 4, 4, 1, 64, 2> TileHalfB;
 constexpr int kTile = 256;             // Tile::EA == Tile::EB
 constexpr int kBK = Tile::BK;
 constexpr int kThreads = Tile::kThreads;
@@ -64,8 +66,9 @@ inline int xcd_grid(int total) { return kNumXcd * ((total + kNumXcd - 1) / kNumX
 // tiles, so that the 32 workgroups resident on an XCD form an 8 x 4 rectangle of tiles (12 distinct
 // panels for 32 workgroups) instead of a 2 x 16 strip (18 panels).  Returns false for padding workgroups.
 constexpr int kFastGroup = 4;
-__device__ __forceinline__ bool xcd_tile_2d(int n_slow, int n_fast, int* slow, int* fast) {
-  const int x = blockIdx.x % kNumXcd, q = blockIdx.x / kNumXcd;
+__device__ __forceinline__ bool xcd_tile_2d(int n_slow, int n_fast, int* slow, int* fast, int block = -1) {
+  if (block < 0) block = blockIdx.x;       // a kernel that serves several tile spaces passes its own index
+  const int x = block % kNumXcd, q = block / kNumXcd;
   const int spx = (n_slow + kNumXcd - 1) / kNumXcd;          // slow tiles per XCD
   if (q >= spx * n_fast) return false;
   const int full = n_fast / kFastGroup, rem = n_fast - full * kFastGroup;
@@ -405,14 +408,13 @@ __global__ __launch_bounds__(256) void k_bwd_dh_reduce(const float* __restrict__
 //   chunks and dW is read and written half as often as there are chunks.  The running sum is
 //   kept unscaled; the last pass multiplies by gamma = grad_loss / N_valid.  Passes run in order
 //   on one stream, so the summation order is fixed and dW is reproducible bit for bit.
+//   The body is a device function so that the MLP path can serve its three weight gradients from one launch.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void k_bwd_gemm_dw(
-    const __bf16* __restrict__ G, int ldg, const __bf16* __restrict__ Hc, int rows, int d, int V,
-    int n_vt, int n_jt, int accumulate, int last, const long long* __restrict__ n_valid, float grad_loss,
-    float* __restrict__ dW) {
-  extern __shared__ __attribute__((aligned(1024))) char smem[];
-  int vt, jt;
-  if (!xcd_tile_2d(n_vt, n_jt, &vt, &jt)) return;
+// G: [rows][ldg], columns [0, g_cols) readable (v < V of them used); Hc: [rows][ldh], columns [0, d) used;
+// dW: [V][ldw], columns [0, d) written
+__device__ __forceinline__ void dw_tile(
+    const __bf16* __restrict__ G, int ldg, int g_cols, const __bf16* __restrict__ Hc, int ldh, int rows, int d, int V,
+    int vt, int jt, int accumulate, float scale, float* __restrict__ dW, int ldw, char* smem) {
   const int v0 = vt * kTile, j0 = jt * kTile;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -428,7 +430,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dw(
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int v = v0 + wa * 128 + 32 * t + a_index_in_tile<false>(r, lane);
-          acc[t][u][r] = (v < V && j < d) ? dW[(size_t)v * d + j] : 0.f;
+          acc[t][u][r] = (v < V && j < d) ? dW[(size_t)v * ldw + j] : 0.f;
         }
       }
   } else {
@@ -436,11 +438,10 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dw(
   }
   PanelKS<Tile, kTile, kTA> pa;
   PanelKS<Tile, kTile, kTB> pb;
-  pa.init(G + v0, ldg, rows, ldg - v0, wave, lane, wa);
-  pb.init(Hc + j0, d, rows, d - j0, wave, lane, wb);
+  pa.init(G + v0, ldg, rows, g_cols - v0, wave, lane, wa);
+  pb.init(Hc + j0, ldh, rows, d - j0, wave, lane, wb);
   gemm_mainloop_pp<Tile>(acc, pa, pb, smem, 0, rows, wa);
 
-  const float scale = last ? gamma_of(n_valid, grad_loss) : 1.0f;
 #pragma unroll
   for (int t = 0; t < kTA; ++t)
 #pragma unroll
@@ -449,9 +450,20 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dw(
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int v = v0 + wa * 128 + 32 * t + a_index_in_tile<false>(r, lane);
-        if (v < V && j < d) dW[(size_t)v * d + j] = scale * acc[t][u][r];
+        if (v < V && j < d) dW[(size_t)v * ldw + j] = scale * acc[t][u][r];
       }
     }
+}
+
+__global__ __launch_bounds__(kThreads) void k_bwd_gemm_dw(
+    const __bf16* __restrict__ G, int ldg, const __bf16* __restrict__ Hc, int rows, int d, int V,
+    int n_vt, int n_jt, int accumulate, int last, const long long* __restrict__ n_valid, float grad_loss,
+    float* __restrict__ dW) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  int vt, jt;
+  if (!xcd_tile_2d(n_vt, n_jt, &vt, &jt)) return;
+  const float scale = last ? gamma_of(n_valid, grad_loss) : 1.0f;
+  dw_tile(G, ldg, ldg, Hc, d, rows, d, V, vt, jt, accumulate, scale, dW, d, smem);
 }
 
 }  // namespace mst

@@ -55,8 +55,9 @@ void set_kernel_attributes() {
   set((const void*)k_mlp_gateup<false>);
   set((const void*)k_mlp_gateup<true>);
   set((const void*)k_mlp_gemm_nt);
-  set((const void*)k_mlp_gemm_nn);
-  set((const void*)k_bwd_gemm_dw);
+  set((const void*)k_mlp_gemm_nn<Tile>);
+  set((const void*)k_mlp_gemm_nn<TileHalfB>);
+  set((const void*)k_mlp_dw3);
 }
 
 mst_status check_launch() { return hipGetLastError() == hipSuccess ? MST_OK : MST_ERR_LAUNCH; }
@@ -72,6 +73,49 @@ mst_status prepare_device() {
 int rows_of(const Plan& p, int i) {
   const int64_t r0 = (int64_t)i * p.C;
   return (int)((p.S - r0) < p.C ? (p.S - r0) : p.C);
+}
+
+
+constexpr int kNumCu = 256;   // MI355X compute units; one workgroup is resident per CU
+
+// Tail of the workgroup grid.  A GEMM of n_a x n_b block tiles runs in rounds of kNumCu workgroups; when the
+// last round would be at most half full, the tiles of that round (whole tile rows of the A side, else whole
+// tile columns of the B side) are cut in two along the B side (256 x 128 tiles) and launched separately, so
+// that the last round is full and shorter.
+struct Tail { int a_tail, b_tail; };
+Tail tail_split(int n_a, int n_b) {
+  const int total = n_a * n_b, rem = total % kNumCu;
+  if (total < kNumCu || rem == 0 || 2 * rem > kNumCu) return {0, 0};
+  if (rem % n_b == 0) return {rem / n_b, 0};
+  if (rem % n_a == 0) return {0, rem / n_a};
+  return {0, 0};
+}
+
+// out[rows][N] (+)= P1 Q1 (+ P2 Q2), Q: [K][ldq] with N columns used
+void launch_nn(hipStream_t st, const __bf16* P1, const __bf16* Q1, const __bf16* P2, const __bf16* Q2,
+               int ldp, int ldq, int rows, int N, int K, __bf16* out, int ldo) {
+  const int n_nt = (N + kTile - 1) / kTile, n_st = (rows + kTile - 1) / kTile;
+  const Tail tl = tail_split(n_nt, n_st);
+  const int nt_full = n_nt - tl.a_tail;        // only a split of the A side (columns of Q) is used here
+  const int n_full = tl.a_tail ? nt_full * kTile : N;
+  hipLaunchKernelGGL(k_mlp_gemm_nn<Tile>, dim3(xcd_grid_super(nt_full, n_st)), dim3(kThreads), kLdsBytes, st,
+                     P1, Q1, P2, Q2, ldp, ldq, rows, n_full, K, n_st, nt_full, out, ldo);
+  if (tl.a_tail) {
+    const int n_sh = (rows + TileHalfB::EB - 1) / TileHalfB::EB;
+    hipLaunchKernelGGL(k_mlp_gemm_nn<TileHalfB>, dim3(xcd_grid_super(tl.a_tail, n_sh)), dim3(kThreads),
+                       TileHalfB::kLds, st, P1, Q1 + n_full, P2, Q2 ? Q2 + n_full : Q2, ldp, ldq, rows, N - n_full, K,
+                       n_sh, tl.a_tail, out + n_full, ldo);
+  }
+}
+
+DwProblem dw_problem(const __bf16* G, int ldg, const __bf16* H, int ldh, int d, int V, float* dW) {
+  DwProblem q;
+  q.G = G; q.ldg = ldg; q.H = H; q.ldh = ldh; q.d = d; q.V = V;
+  q.n_vt = (V + kTile - 1) / kTile;
+  q.n_jt = (d + kTile - 1) / kTile;
+  q.grid = xcd_grid_2d(q.n_vt, q.n_jt);
+  q.dW = dW;
+  return q;
 }
 
 }  // namespace
@@ -161,7 +205,6 @@ mst_status mst_mlp_bwd(const void* X, const void* Wg, const void* Wu, const void
   __bf16* bufU = reinterpret_cast<__bf16*>(ws + p.slot);      // dU
   __bf16* bufA = reinterpret_cast<__bf16*>(ws + 2 * p.slot);  // A
   const int dI = (int)p.I, dd = (int)p.d;
-  const long long* no_count = nullptr;
 
   // Algorithm 3: loop over the mini-sequences; dX_i lands in its row range, the weight gradients accumulate
   for (int i = 0; i < p.n_chunks; ++i) {
@@ -172,9 +215,7 @@ mst_status mst_mlp_bwd(const void* X, const void* Wg, const void* Wu, const void
     const int acc = i > 0 ? 1 : 0;
     {
       Scope sc(st, MST_MLP_K_DA);
-      hipLaunchKernelGGL(k_mlp_gemm_nn, dim3(xcd_grid_super(p.n_it, n_st)), dim3(kThreads), kLdsBytes, st,
-                         dOc, Wdb, (const __bf16*)nullptr, (const __bf16*)nullptr, dd, dI, rows, dI, dd,
-                         n_st, p.n_it, bufG, dI);
+      launch_nn(st, dOc, Wdb, nullptr, nullptr, dd, dI, rows, dI, dd, bufG, dI);
     }
     {
       Scope sc(st, MST_MLP_K_GATEUP_BWD);
@@ -183,24 +224,16 @@ mst_status mst_mlp_bwd(const void* X, const void* Wg, const void* Wu, const void
     }
     {
       Scope sc(st, MST_MLP_K_DX);
-      hipLaunchKernelGGL(k_mlp_gemm_nn, dim3(xcd_grid_super(p.n_dt, n_st)), dim3(kThreads), kLdsBytes, st,
-                         (const __bf16*)bufG, Wgb, (const __bf16*)bufU, Wub, dI, dd, rows, dd, dI,
-                         n_st, p.n_dt, dXb + r0 * p.d, dd);
+      launch_nn(st, bufG, Wgb, bufU, Wub, dI, dd, rows, dd, dI, dXb + r0 * p.d, dd);
     }
     {
       Scope sc(st, MST_MLP_K_DW);
-      hipLaunchKernelGGL(k_bwd_gemm_dw, dim3(xcd_grid_2d(p.n_it, p.n_dt)), dim3(kThreads), kLdsBytes, st,
-                         (const __bf16*)bufG, dI, Xc, rows, dd, dI, p.n_it, p.n_dt, acc, 0, no_count, 1.0f, dWg);
-    }
-    {
-      Scope sc(st, MST_MLP_K_DW);
-      hipLaunchKernelGGL(k_bwd_gemm_dw, dim3(xcd_grid_2d(p.n_it, p.n_dt)), dim3(kThreads), kLdsBytes, st,
-                         (const __bf16*)bufU, dI, Xc, rows, dd, dI, p.n_it, p.n_dt, acc, 0, no_count, 1.0f, dWu);
-    }
-    {
-      Scope sc(st, MST_MLP_K_DW);
-      hipLaunchKernelGGL(k_bwd_gemm_dw, dim3(xcd_grid_2d(p.n_dt, p.n_it)), dim3(kThreads), kLdsBytes, st,
-                         dOc, dd, (const __bf16*)bufA, rows, dI, dd, p.n_dt, p.n_it, acc, 0, no_count, 1.0f, dWd);
+      DwProblems ps;
+      ps.p[0] = dw_problem(bufG, dI, Xc, dd, dd, dI, dWg);     // dWg [I][d] (+)= dG^T X
+      ps.p[1] = dw_problem(bufU, dI, Xc, dd, dd, dI, dWu);     // dWu [I][d] (+)= dU^T X
+      ps.p[2] = dw_problem(dOc, dd, bufA, dI, dI, dd, dWd);    // dWd [d][I] (+)= dO^T A
+      hipLaunchKernelGGL(k_mlp_dw3, dim3(ps.p[0].grid + ps.p[1].grid + ps.p[2].grid), dim3(kThreads), kLdsBytes, st,
+                         ps, rows, acc);
     }
   }
   return check_launch();

@@ -167,8 +167,10 @@ __global__ __launch_bounds__(kThreads) void k_mlp_gemm_nt(
 // ---------------------------------------------------------------------------
 // out[s][n] = sum_k P1[s][k] Q1[k][n] (+ sum_k P2[s][k] Q2[k][n])   (Q K-strided)
 //   used for dA = dO Wd (one term, K = d) and dX = dG Wg + dU Wu (two terms, K = I each)
-//   A side = s (rows of P), B side = n (columns of Q)
+//   A side = n (columns of Q, read transposed with the row permutation, so a lane holds 16 consecutive n
+//   and stores 32 bytes), B side = s (rows of P).  T: Tile, or TileHalfB for a partly filled last round.
 // ---------------------------------------------------------------------------
+template <class T>
 __global__ __launch_bounds__(kThreads) void k_mlp_gemm_nn(
     const __bf16* __restrict__ P1, const __bf16* __restrict__ Q1,
     const __bf16* __restrict__ P2, const __bf16* __restrict__ Q2,
@@ -176,39 +178,68 @@ __global__ __launch_bounds__(kThreads) void k_mlp_gemm_nn(
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   int nt, st;
   if (!xcd_tile_super(n_nt, n_st, &nt, &st)) return;
-  const int n0 = nt * kTile, s0 = st * kTile;
+  const int n0 = nt * T::EA, s0 = st * T::EB;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int wa = wave >> 2, wb = wave & 3;
+  const int wa = wave / T::WB, wb = wave % T::WB;
 
-  f32x16 acc[kTA][kTB];
-  zero_acc<kTA, kTB>(acc);
+  f32x16 acc[T::TA][T::TB];
+  zero_acc<T::TA, T::TB>(acc);
   {
-    PanelKC<Tile, kTile, kTA, false> pa;
-    PanelKS<Tile, kTile, kTB> pb;
-    pa.init(P1 + (size_t)s0 * ldp, ldp, rows - s0, K, wave, lane, wa);
-    pb.init(Q1 + n0, ldq, K, N - n0, wave, lane, wb);
-    gemm_mainloop_pp<Tile>(acc, pa, pb, smem, 0, K, wa);
+    PanelKS<T, T::EA, T::TA, true> pa;
+    PanelKC<T, T::EB, T::TB, false> pb;
+    pa.init(Q1 + n0, ldq, K, N - n0, wave, lane, wa);
+    pb.init(P1 + (size_t)s0 * ldp, ldp, rows - s0, K, wave, lane, wb);
+    gemm_mainloop_pp<T>(acc, pa, pb, smem, 0, K, wa);
   }
   if (P2 != nullptr) {
-    PanelKC<Tile, kTile, kTA, false> pa;
-    PanelKS<Tile, kTile, kTB> pb;
-    pa.init(P2 + (size_t)s0 * ldp, ldp, rows - s0, K, wave, lane, wa);
-    pb.init(Q2 + n0, ldq, K, N - n0, wave, lane, wb);
-    gemm_mainloop_pp<Tile>(acc, pa, pb, smem, 0, K, wa);
+    PanelKS<T, T::EA, T::TA, true> pa;
+    PanelKC<T, T::EB, T::TB, false> pb;
+    pa.init(Q2 + n0, ldq, K, N - n0, wave, lane, wa);
+    pb.init(P2 + (size_t)s0 * ldp, ldp, rows - s0, K, wave, lane, wb);
+    gemm_mainloop_pp<T>(acc, pa, pb, smem, 0, K, wa);
   }
 
 #pragma unroll
-  for (int t = 0; t < kTA; ++t)
+  for (int u = 0; u < T::TB; ++u) {
+    const int s_local = s0 + wb * (32 * T::TB) + 32 * u + (lane & 31);
+    if (s_local >= rows) continue;
+    __bf16* orow = out + (size_t)s_local * ldo;
 #pragma unroll
-    for (int u = 0; u < kTB; ++u) {
-      const int n = n0 + wb * 64 + 32 * u + (lane & 31);
+    for (int t = 0; t < T::TA; ++t) {
+      const int nb = n0 + wa * (32 * T::TA) + 32 * t + 16 * (lane >> 5);
+      bf16x8 lo, hi;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int s_local = s0 + wa * 128 + 32 * t + a_index_in_tile<false>(r, lane);
-        if (s_local < rows && n < N) out[(size_t)s_local * ldo + n] = (__bf16)acc[t][u][r];
+        if (r < 8) lo[r] = (__bf16)acc[t][u][r]; else hi[r - 8] = (__bf16)acc[t][u][r];
       }
+      if (nb < N) *reinterpret_cast<bf16x8*>(orow + nb) = lo;          // N % 8 == 0
+      if (nb + 8 < N) *reinterpret_cast<bf16x8*>(orow + nb + 8) = hi;
     }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// the three weight gradients of a chunk from one launch: dWg (+)= dG^T X, dWu (+)= dU^T X, dWd (+)= dO^T A.
+//   Each is a tile space of its own (the LM-head's dW tile body); the workgroup index selects the problem.
+//   One launch instead of three leaves one partly filled last round of workgroups instead of three
+//   (3 x 896 tiles = 10.5 rounds of 256 instead of 3 x 4 at the Llama3-8B shape).
+// ---------------------------------------------------------------------------
+struct DwProblem {
+  const __bf16* G; int ldg;      // [rows][ldg], V columns used
+  const __bf16* H; int ldh;      // [rows][ldh], d columns used
+  int d, V, n_vt, n_jt, grid;    // grid = xcd_grid_2d(n_vt, n_jt)
+  float* dW;                     // [V][d]
+};
+struct DwProblems { DwProblem p[3]; };
+__global__ __launch_bounds__(kThreads) void k_mlp_dw3(DwProblems ps, int rows, int accumulate) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  int b = blockIdx.x, which = 0;
+  if (b >= ps.p[0].grid) { b -= ps.p[0].grid; which = 1; if (b >= ps.p[1].grid) { b -= ps.p[1].grid; which = 2; } }
+  const DwProblem& q = ps.p[which];
+  int vt, jt;
+  if (!xcd_tile_2d(q.n_vt, q.n_jt, &vt, &jt, b)) return;
+  dw_tile(q.G, q.ldg, q.ldg, q.H, q.ldh, rows, q.d, q.V, vt, jt, accumulate, 1.0f, q.dW, q.d, smem);
 }
 
 }  // namespace mst
