@@ -108,6 +108,26 @@ mst_status mst_workspace_bytes(int64_t S, int64_t d, int64_t V, int32_t M,
 int32_t mst_suggest_m(int64_t S, int64_t d, int64_t V);
 
 /*
+ * Next-token alignment of labels (optional helper; device, enqueued on `stream`).
+ * Algorithm 2 takes hidden states X and labels L that are already aligned row
+ * by row; the paper is silent on the causal shift that language-model training
+ * applies before the head.  For B sequences of L positions each, folded into
+ * S = B * L rows, this writes the label of row (b, t) as the token that
+ * follows it:
+ *
+ *     labels_out[b * L + t] = labels_in[b * L + t + 1]     for t < L - 1
+ *     labels_out[b * L + L - 1] = ignore_index             (nothing follows the last position)
+ *
+ * so that the unshifted H [B * L, d] and labels_out can be handed to the two
+ * calls below.  Values of labels_in equal to ignore_index move with the shift.
+ * labels_in and labels_out: int32 [B * L], 4-byte aligned, must not overlap.
+ * Errors: MST_ERR_NULL_POINTER, MST_ERR_BAD_SHAPE (B or L not positive, or
+ * B * L >= 2^40), MST_ERR_ALIGNMENT.
+ */
+mst_status mst_shift_labels(const int32_t* labels_in, int64_t B, int64_t L, int32_t ignore_index,
+                            int32_t* labels_out, void* stream);
+
+/*
  * Forward: mini-sequence LM-head loss (Algorithm 2).
  *   H        bf16 [S, d] row-major
  *   W        bf16 [V, d] row-major

@@ -206,3 +206,16 @@ def lmhead_ce_chunked(H, W, labels, M, ignore_index=-100, grad_loss=1.0):
         dH[r0:r1] = g @ W
         dW += g.T @ H[r0:r1]
     return dict(loss=loss, n_valid=n_valid, dH=dH, dW=dW)
+
+
+def shift_labels(labels, B: int, L: int, ignore_index: int = -100) -> np.ndarray:
+    """Next-token alignment for B sequences of L positions folded into B * L rows: the label of position t
+    is the entry at t + 1; the last position of every sequence has no successor and is ignored.  (The paper's
+    Algorithm 2 takes aligned X and L and is silent on this step; this is the alignment language-model
+    training applies before the head, written out as its definition.)"""
+    labels = np.asarray(labels)
+    if B <= 0 or L <= 0 or labels.shape != (B * L,):
+        raise ValueError("labels must have B * L entries")
+    out = np.full((B, L), ignore_index, dtype=labels.dtype)
+    out[:, : L - 1] = labels.reshape(B, L)[:, 1:]
+    return out.reshape(B * L)

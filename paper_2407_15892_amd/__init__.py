@@ -6,6 +6,7 @@ from .binding import (  # noqa: F401
     mst_lmhead_ce_fwd,
     mst_profile_collect,
     mst_profile_enable,
+    mst_shift_labels,
     mst_strerror,
     mst_suggest_m,
     mst_version,

@@ -53,6 +53,8 @@ def load_library() -> ctypes.CDLL:
                                         c.POINTER(c.c_size_t), c.POINTER(c.c_size_t)]
     lib.mst_suggest_m.restype = c.c_int32
     lib.mst_suggest_m.argtypes = [c.c_int64, c.c_int64, c.c_int64]
+    lib.mst_shift_labels.restype = c.c_int
+    lib.mst_shift_labels.argtypes = [c.c_void_p, c.c_int64, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p]
     lib.mst_lmhead_ce_fwd.restype = c.c_int
     lib.mst_lmhead_ce_fwd.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int64, c.c_int64,
                                       c.c_int32, c.c_int32, c.c_void_p, c.c_size_t,
@@ -94,6 +96,13 @@ def mst_workspace_bytes(S: int, d: int, V: int, M: int):
 def mst_suggest_m(S: int, d: int, V: int) -> int:
     """Chunk count advised by the paper's M = V / d rule, kept to chunks of at least 256 rows."""
     return int(load_library().mst_suggest_m(S, d, V))
+
+
+def mst_shift_labels(labels_in, B: int, L: int, ignore_index: int, labels_out, stream=None) -> None:
+    """Enqueue the next-token alignment: labels_out[b, t] = labels_in[b, t + 1], ignore_index at t = L - 1.
+    Both int32 device tensors of B * L elements."""
+    _check(load_library().mst_shift_labels(_ptr(labels_in), B, L, ignore_index, _ptr(labels_out),
+                                           _stream_handle(stream)))
 
 
 def mst_workspace_bytes_status(S: int, d: int, V: int, M: int) -> int:

@@ -169,6 +169,19 @@ int32_t mst_suggest_m(int64_t S, int64_t d, int64_t V) {
   return (int32_t)m;
 }
 
+mst_status mst_shift_labels(const int32_t* labels_in, int64_t B, int64_t L, int32_t ignore_index,
+                            int32_t* labels_out, void* stream) {
+  if (B <= 0 || L <= 0 || B >= (int64_t(1) << 40) / L) return MST_ERR_BAD_SHAPE;
+  if (!labels_in || !labels_out) return MST_ERR_NULL_POINTER;
+  if (misaligned(labels_in, 4) || misaligned(labels_out, 4)) return MST_ERR_ALIGNMENT;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return MST_ERR_NO_DEVICE;
+  const long long n = (long long)(B * L);
+  hipLaunchKernelGGL(k_shift_labels, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
+                     reinterpret_cast<hipStream_t>(stream), labels_in, n, (long long)L, ignore_index, labels_out);
+  return check_launch();
+}
+
 mst_status mst_workspace_bytes(int64_t S, int64_t d, int64_t V, int32_t M, size_t* fwd_bytes, size_t* bwd_bytes) {
   Plan p;
   mst_status s = make_plan(S, d, V, M, &p);

@@ -118,6 +118,14 @@ __global__ __launch_bounds__(1024) void k_label_scan(const int* __restrict__ lab
   }
 }
 
+// next-token alignment: the label of position t of a sequence is the token at t + 1; the last position has none
+__global__ __launch_bounds__(256) void k_shift_labels(const int* __restrict__ in, long long n, long long L,
+                                                      int ignore_index, int* __restrict__ out) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  out[i] = (i % L == L - 1) ? ignore_index : in[i + 1];
+}
+
 // ---------------------------------------------------------------------------
 // forward: logits tile + running log-sum-exp partials + target logit
 //   A side = vocabulary (W rows), B side = chunk rows (H rows): a lane owns one

@@ -227,3 +227,37 @@ def test_repeated_calls_reuse_the_same_buffers():
     assert abs(float(loss) - ref["loss"]) <= LOSS_RTOL * abs(ref["loss"])
     assert np.abs(dW.cpu().numpy() - ref["dW"]).max() <= GRAD_TOL * np.abs(ref["dW"]).max()
     assert np.abs(bf2f(dH) - ref["dH"]).max() <= GRAD_TOL * np.abs(ref["dH"]).max()
+
+
+@pytest.mark.parametrize("B,L", [(1, 1), (4, 1), (1, 257), (3, 1000), (64, 513), (2, 100003)])
+def test_shift_labels_is_bit_exact(B, L):
+    import torch
+    import paper_2407_15892_amd as mst
+    rng = np.random.default_rng(B * 1000 + L)
+    tok = rng.integers(0, 128256, size=B * L).astype(np.int32)
+    tok[rng.integers(0, B * L, size=max(1, B * L // 50))] = -100
+    ref = orc.shift_labels(tok, B, L)
+    t_in = torch.from_numpy(tok).cuda()
+    t_out = torch.full((B * L + 8,), 12345, dtype=torch.int32, device="cuda")     # guard elements after the end
+    mst.mst_shift_labels(t_in, B, L, -100, t_out)
+    torch.cuda.synchronize()
+    got = t_out.cpu().numpy()
+    assert np.array_equal(got[: B * L], ref)
+    assert (got[B * L:] == 12345).all()
+
+
+def test_shifted_labels_feed_the_forward_pass():
+    import torch
+    import paper_2407_15892_amd as mst
+    DeviceRun, _ = _harness()
+    B, L = 4, 75
+    inp = mi.make_inputs(mi.custom_config(B * L, 64, 520, 3, index=77, ignore_frac=0.1))
+    shifted = orc.shift_labels(inp.labels, B, L)
+    ref_loss = orc.lmhead_ce_forward(inp.H_f64(), inp.W_f64(), shifted)[0]
+    run = DeviceRun(inp)
+    out = torch.empty_like(run.labels)
+    mst.mst_shift_labels(run.labels, B, L, inp.ignore_index, out)
+    run.labels = out
+    loss, _, nv = run.forward()
+    assert nv == int((shifted != -100).sum())
+    assert abs(loss - ref_loss) <= LOSS_RTOL * abs(ref_loss)

@@ -105,3 +105,14 @@ def test_chunk_count_policy(mst):
     for S, d, V in [(8192, 4096, 128256), (777, 264, 1000), (64, 8, 40)]:
         M = mst.mst_suggest_m(S, d, V)
         assert 1 <= M <= S and mst.binding.mst_workspace_bytes_status(S, d, V, M) == 0
+
+
+def test_shift_labels_argument_errors(mst):
+    lib = mst.load_library()
+    fake = 0x1000
+    assert lib.mst_shift_labels(None, 2, 3, -100, fake, None) == -1
+    assert lib.mst_shift_labels(fake, 2, 3, -100, None, None) == -1
+    assert lib.mst_shift_labels(fake, 0, 3, -100, fake, None) == -2
+    assert lib.mst_shift_labels(fake, 2, 0, -100, fake, None) == -2
+    assert lib.mst_shift_labels(fake, 1 << 30, 1 << 30, -100, fake, None) == -2
+    assert lib.mst_shift_labels(fake + 2, 2, 3, -100, fake, None) == -5

@@ -335,3 +335,28 @@ def test_golden_config1_values_are_reproduced():
     assert int(inp.H_bits.astype(np.uint64).sum()) == gold["H_bits_sum"]
     assert int(inp.W_bits.astype(np.uint64).sum()) == gold["W_bits_sum"]
     assert int(inp.labels.astype(np.int64).sum()) == gold["labels_sum"]
+
+
+def test_shift_labels_matches_the_sliced_next_token_loss():
+    """Library cross-check of the alignment helper: the loss over unshifted hidden states with shifted labels
+    equals the usual next-token loss that slices logits[:, :-1] against labels[:, 1:]."""
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(31)
+    B, L, d, V = 3, 7, 5, 11
+    H = rng.standard_normal((B * L, d))
+    W = rng.standard_normal((V, d))
+    tok = rng.integers(0, V, size=B * L).astype(np.int32)
+    tok[[4, 9]] = -100                                   # masked positions move with the shift
+    y = orc.shift_labels(tok, B, L)
+    assert list(y.reshape(B, L)[:, -1]) == [-100] * B
+    assert (y.reshape(B, L)[:, :-1] == tok.reshape(B, L)[:, 1:]).all()
+    loss = orc.lmhead_ce_forward(H, W, y)[0]
+    logits = torch.tensor(H @ W.T).reshape(B, L, V)
+    ref = torch.nn.functional.cross_entropy(logits[:, :-1].reshape(-1, V),
+                                            torch.tensor(tok.reshape(B, L)[:, 1:].reshape(-1), dtype=torch.long),
+                                            ignore_index=-100)
+    assert loss == pytest.approx(float(ref), rel=1e-12)
+    # degenerate: sequences of one position have no successor at all
+    assert (orc.shift_labels(np.arange(4, dtype=np.int32), 4, 1) == -100).all()
+    with pytest.raises(ValueError):
+        orc.shift_labels(tok, B, L + 1)
