@@ -69,10 +69,10 @@ MLP_FLOP_UNITS = {"gateup": 4.0, "down": 2.0, "da": 2.0, "gateup_bwd": 4.0, "dx"
 MLP_PMC_TRAFFIC_BYTES = {
     (2, "gateup"): 1.410e9 + 0.118e9,
     (2, "down"): 0.705e9 + 0.035e9,
-    (2, "da"): 0.712e9 + 0.126e9,
+    (2, "da"): 0.783e9 + 0.133e9,
     (2, "gateup_bwd"): 1.534e9 + 0.473e9,
-    (2, "dx"): 1.412e9 + 0.036e9,
-    (2, "dw"): 1.069e9 + 0.235e9,
+    (2, "dx"): 1.413e9 + 0.039e9,
+    (2, "dw"): 3.376e9 + 0.705e9,
 }
 
 
