@@ -38,6 +38,24 @@ PMC_TRAFFIC_BYTES = {
 }
 
 
+def mfma_probe(mst, torch):
+    """Empirical matrix-core rate of this chip with no data movement: a register-resident MFMA loop, all-zero
+    operands and pseudo-random operands (the chip is power limited, so the two differ)."""
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+    out = {}
+    for name, scale in (("zero_operands", 0.0), ("random_operands", 1.0)):
+        mst.mst_mfma_probe(512, 200, scale, sink, stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        flop = mst.mst_mfma_probe(512, 6000, scale, sink, stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        out[name + "_tflops"] = flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    out["what"] = "512 workgroups x 8 waves x 6000 x 16 v_mfma_f32_32x32x16_bf16 on register-resident operands"
+    return out
+
+
 def cpu_baseline(inp, sample_rows: int):
     """The fp64 oracle as it stands, timed on the host cores on the first `sample_rows` tokens."""
     import numpy as np
@@ -328,6 +346,7 @@ def main() -> int:
         "loss": float(loss.item()), "n_valid": int(nv.item()),
         "roofline": roofline, "kernels": kernels, "input_generation_s": gen_s,
     }
+    out["empirical_mfma_peak"] = mfma_probe(mst, torch)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(inp, args.cpu_sample_rows)
     print(json.dumps(out))

@@ -163,6 +163,19 @@ mst_status mst_lmhead_ce_bwd(const void* H, const void* W, const int32_t* labels
                              void* stream);
 
 /*
+ * Matrix-core probe (measurement aid, not part of the path).  Enqueues a kernel in
+ * which every wave of `blocks` workgroups of 512 threads issues iters * 16
+ * v_mfma_f32_32x32x16_bf16 instructions on register-resident operands (no LDS, no
+ * global loads), i.e. blocks * 8 * iters * 16 * 32768 flop in total.  Operands are
+ * all zero when `scale` is 0 and pseudo-random of that magnitude otherwise; the
+ * sustained rate depends on it because the chip is power limited.  `sink`: one
+ * device float, never written in practice (it keeps the loop alive).  The caller
+ * times the launch with events on `stream`.
+ * Errors: MST_ERR_NULL_POINTER, MST_ERR_BAD_SHAPE (blocks or iters not in [1, 2^20]).
+ */
+mst_status mst_mfma_probe(int32_t blocks, int32_t iters, float scale, float* sink, void* stream);
+
+/*
  * Per-kernel timing (host).  When enabled, every kernel launch of the two calls
  * above is bracketed by HIP events on the caller's stream.  mst_profile_collect
  * waits for the recorded events, adds the elapsed milliseconds and launch

@@ -4,6 +4,7 @@ from .binding import (  # noqa: F401
     load_library,
     mst_lmhead_ce_bwd,
     mst_lmhead_ce_fwd,
+    mst_mfma_probe,
     mst_profile_collect,
     mst_profile_enable,
     mst_shift_labels,

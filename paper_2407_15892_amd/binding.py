@@ -53,6 +53,8 @@ def load_library() -> ctypes.CDLL:
                                         c.POINTER(c.c_size_t), c.POINTER(c.c_size_t)]
     lib.mst_suggest_m.restype = c.c_int32
     lib.mst_suggest_m.argtypes = [c.c_int64, c.c_int64, c.c_int64]
+    lib.mst_mfma_probe.restype = c.c_int
+    lib.mst_mfma_probe.argtypes = [c.c_int32, c.c_int32, c.c_float, c.c_void_p, c.c_void_p]
     lib.mst_shift_labels.restype = c.c_int
     lib.mst_shift_labels.argtypes = [c.c_void_p, c.c_int64, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p]
     lib.mst_lmhead_ce_fwd.restype = c.c_int
@@ -96,6 +98,12 @@ def mst_workspace_bytes(S: int, d: int, V: int, M: int):
 def mst_suggest_m(S: int, d: int, V: int) -> int:
     """Chunk count advised by the paper's M = V / d rule, kept to chunks of at least 256 rows."""
     return int(load_library().mst_suggest_m(S, d, V))
+
+
+def mst_mfma_probe(blocks: int, iters: int, scale: float, sink, stream=None) -> float:
+    """Enqueue the register-resident MFMA loop; returns the flop it executes (time it with events)."""
+    _check(load_library().mst_mfma_probe(blocks, iters, float(scale), _ptr(sink), _stream_handle(stream)))
+    return float(blocks) * 8 * iters * 16 * 32768.0
 
 
 def mst_shift_labels(labels_in, B: int, L: int, ignore_index: int, labels_out, stream=None) -> None:

@@ -169,6 +169,16 @@ int32_t mst_suggest_m(int64_t S, int64_t d, int64_t V) {
   return (int32_t)m;
 }
 
+mst_status mst_mfma_probe(int32_t blocks, int32_t iters, float scale, float* sink, void* stream) {
+  if (blocks < 1 || blocks > (1 << 20) || iters < 1 || iters > (1 << 20)) return MST_ERR_BAD_SHAPE;
+  if (!sink) return MST_ERR_NULL_POINTER;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return MST_ERR_NO_DEVICE;
+  hipLaunchKernelGGL(k_mfma_probe, dim3(blocks), dim3(kThreads), 0, reinterpret_cast<hipStream_t>(stream),
+                     sink, iters, scale);
+  return check_launch();
+}
+
 mst_status mst_shift_labels(const int32_t* labels_in, int64_t B, int64_t L, int32_t ignore_index,
                             int32_t* labels_out, void* stream) {
   if (B <= 0 || L <= 0 || B >= (int64_t(1) << 40) / L) return MST_ERR_BAD_SHAPE;

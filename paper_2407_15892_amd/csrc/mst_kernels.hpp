@@ -118,6 +118,40 @@ __global__ __launch_bounds__(1024) void k_label_scan(const int* __restrict__ lab
   }
 }
 
+// register-resident MFMA loop: the matrix-core rate the chip sustains without any data movement
+__global__ __launch_bounds__(kThreads) void k_mfma_probe(float* sink, int iters, float scale) {
+  f32x16 acc[kTA][kTB];
+  zero_acc<kTA, kTB>(acc);
+  bf16x8 a[8], b[8];
+  uint32_t s = threadIdx.x * 2654435761u + blockIdx.x * 40503u + 12345u;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      s = s * 1664525u + 1013904223u;
+      a[i][e] = (__bf16)(scale * ((int)(s >> 8) % 20001 - 10000) * 1e-4f);
+      s = s * 1664525u + 1013904223u;
+      b[i][e] = (__bf16)(scale * ((int)(s >> 8) % 20001 - 10000) * 1e-4f);
+    }
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+      for (int t = 0; t < kTA; ++t)
+#pragma unroll
+        for (int u = 0; u < kTB; ++u)
+          acc[t][u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(t + 4 * kk) & 7], b[(u + 2 * t + 4 * kk) & 7], acc[t][u], 0, 0, 0);
+  }
+  float tot = 0.f;
+#pragma unroll
+  for (int t = 0; t < kTA; ++t)
+#pragma unroll
+    for (int u = 0; u < kTB; ++u)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) tot += acc[t][u][r];
+  if (tot == 1.2345e-30f) *sink = tot;
+}
+
 // next-token alignment: the label of position t of a sequence is the token at t + 1; the last position has none
 __global__ __launch_bounds__(256) void k_shift_labels(const int* __restrict__ in, long long n, long long L,
                                                       int ignore_index, int* __restrict__ out) {

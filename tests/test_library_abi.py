@@ -116,3 +116,12 @@ def test_shift_labels_argument_errors(mst):
     assert lib.mst_shift_labels(fake, 2, 0, -100, fake, None) == -2
     assert lib.mst_shift_labels(fake, 1 << 30, 1 << 30, -100, fake, None) == -2
     assert lib.mst_shift_labels(fake + 2, 2, 3, -100, fake, None) == -5
+
+
+def test_mfma_probe_argument_errors(mst):
+    lib = mst.load_library()
+    fake = 0x1000
+    assert lib.mst_mfma_probe(0, 10, 1.0, fake, None) == -2
+    assert lib.mst_mfma_probe(8, 0, 1.0, fake, None) == -2
+    assert lib.mst_mfma_probe(8, (1 << 20) + 1, 1.0, fake, None) == -2
+    assert lib.mst_mfma_probe(8, 10, 1.0, None, None) == -1
