@@ -5,7 +5,8 @@
 // One workgroup of 512 threads (8 wave64s, two per SIMD) owns a 256 x 256
 // output tile.  Operand panels of 256 x 64 bf16 are brought from global memory
 // straight into LDS (buffer loads with the LDS bit, 16 bytes per lane, no
-// register staging), double buffered, and consumed by v_mfma_f32_32x32x16_bf16.
+// register staging), three stages deep for the A operand and two for the B
+// operand (all 160 KB of LDS), and consumed by v_mfma_f32_32x32x16_bf16.
 // The wave grid is 2 (A side) x 4 (B side): a wave accumulates 128 x 64, i.e.
 // 4 x 2 MFMA tiles = 128 fp32 accumulator registers per lane.
 //
@@ -46,7 +47,9 @@ struct Cfg {
   static constexpr int kWaves = WA * WB, kThreads = 64 * kWaves;
   static constexpr int EA = 32 * TA * WA, EB = 32 * TB * WB;
   static constexpr int kPanelA = EA * BK * 2, kPanelB = EB * BK * 2;
-  static constexpr int kStage = kPanelA + kPanelB, kLds = NS * kStage;
+  // LDS stages per operand: the B operand has NS, the A operand one more (its loads are issued one K step earlier)
+  static constexpr int NSA = NS + 1, NSB = NS;
+  static constexpr int kLds = NSA * kPanelA + NSB * kPanelB;
   static constexpr int kKK = BK / 16;
 };
 
@@ -211,77 +214,43 @@ struct PanelKS {
   }
 };
 
-// simple multi-stage loop: one barrier per K step, DMA issued NS-1 steps ahead (always issued; past the
-// end of K the loads are out of range and write zeros into a stage nobody reads)
-template <class C, class PA, class PB>
-__device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[C::TA][C::TB], const PA& pa, const PB& pb,
-                                              char* smem, int k_begin, int k_end) {
-  constexpr int LPW = PA::SPW + PB::SPW;
-  const uint32_t lds0 = lds_addr_of(smem);
-  const int nk = (k_end - k_begin + C::BK - 1) / C::BK;
-#pragma unroll
-  for (int s = 0; s < C::NS - 1; ++s) {
-    pa.issue(lds0 + s * C::kStage, k_begin + s * C::BK);
-    pb.issue(lds0 + s * C::kStage + C::kPanelA, k_begin + s * C::BK);
-  }
-  int cur = 0;                       // stage index of step kt
-  for (int kt = 0; kt < nk; ++kt) {
-    wait_vmcnt<(C::NS - 2) * LPW>();
-    __syncthreads();
-    {
-      int nxt = cur + C::NS - 1; if (nxt >= C::NS) nxt -= C::NS;
-      const int k0 = k_begin + (kt + C::NS - 1) * C::BK;
-      pa.issue(lds0 + nxt * C::kStage, k0);
-      pb.issue(lds0 + nxt * C::kStage + C::kPanelA, k0);
-    }
-    const char* a_panel = smem + cur * C::kStage;
-    const char* b_panel = a_panel + C::kPanelA;
-#pragma unroll
-    for (int kk = 0; kk < C::kKK; ++kk) {
-      bf16x8 a[C::TA], b[C::TB];
-#pragma unroll
-      for (int t = 0; t < C::TA; ++t) a[t] = pa.frag(a_panel, t, kk);
-#pragma unroll
-      for (int u = 0; u < C::TB; ++u) b[u] = pb.frag(b_panel, u, kk);
-#pragma unroll
-      for (int t = 0; t < C::TA; ++t)
-#pragma unroll
-        for (int u = 0; u < C::TB; ++u)
-          acc[t][u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[t], b[u], acc[t][u], 0, 0, 0);
-    }
-    cur = cur + 1 == C::NS ? 0 : cur + 1;
-  }
-  wait_vmcnt<0>();
-  __syncthreads();
-}
-
-// ping-pong loop for 8 waves (WA == 2): waves 0-3 and 4-7 alternate between a memory phase (DMA issue +
-// all fragment reads of a stage) and a compute phase (all MFMAs of the stage), one barrier per phase
+// Ping-pong main loop for 8 waves (WA == 2): waves 0-3 (group 0) and 4-7 (group 1) alternate between a
+// memory phase (global->LDS loads of later stages + all fragment reads of the current stage) and a compute
+// phase (all MFMAs of the stage), one workgroup barrier per phase, group 1 running one phase behind group 0.
+//
+// LDS holds NSA = 3 stages of the A panel and NSB = 2 of the B panel (3 * 32 KB + 2 * 32 KB = all 160 KB
+// of a CU for the 256 x 256 tile).  In the memory phase of step kt a wave issues its B loads for step kt + 1
+// and then its A loads for step kt + 2; the wait that opens step kt + 1 (vmcnt(SPW of A)) lets the A loads
+// of step kt + 2 stay in flight.  So the A operand, which is the one every kernel streams from HBM or the
+// memory-side cache, has two K steps to arrive and the B operand one; with two stages each (one K step for
+// both) the matrix pipe was busy 75 % of the clocks, with loads that are never waited for 98 %.
+// Loads are always issued, also past the end of K: there they are out of range and write zeros into a stage
+// nobody reads.
 template <class C, class PA, class PB>
 __device__ __forceinline__ void gemm_mainloop_pp(f32x16 (&acc)[C::TA][C::TB], const PA& pa, const PB& pb,
                                                  char* smem, int k_begin, int k_end, int group) {
-  constexpr int LPW = PA::SPW + PB::SPW;
-  const uint32_t lds0 = lds_addr_of(smem);
+  static_assert(C::NSA == 3 && C::NSB == 2, "three A stages, two B stages");
+  constexpr int kAhead = PA::SPW;              // loads of one A stage per wave: allowed in flight at a wait
+  const uint32_t ldsA = lds_addr_of(smem), ldsB = ldsA + C::NSA * C::kPanelA;
+  const char* smemB = smem + C::NSA * C::kPanelA;
   const int nk = (k_end - k_begin + C::BK - 1) / C::BK;
-#pragma unroll
-  for (int s = 0; s < C::NS - 1; ++s) {
-    pa.issue(lds0 + s * C::kStage, k_begin + s * C::BK);
-    pb.issue(lds0 + s * C::kStage + C::kPanelA, k_begin + s * C::BK);
-  }
-  wait_vmcnt<(C::NS - 2) * LPW>();
+  pa.issue(ldsA, k_begin);
+  pb.issue(ldsB, k_begin);
+  pa.issue(ldsA + C::kPanelA, k_begin + C::BK);
+  wait_vmcnt<kAhead>();
   __builtin_amdgcn_s_barrier();
   if (group == 1) __builtin_amdgcn_s_barrier();
-  int cur = 0;
+  int ca = 0, cb = 0;                          // stage indices of step kt
   for (int kt = 0; kt < nk; ++kt) {
     // ---- memory phase
     {
-      int nxt = cur + C::NS - 1; if (nxt >= C::NS) nxt -= C::NS;
-      const int k0 = k_begin + (kt + C::NS - 1) * C::BK;
-      pa.issue(lds0 + nxt * C::kStage, k0);
-      pb.issue(lds0 + nxt * C::kStage + C::kPanelA, k0);
+      int na = ca + C::NSA - 1; if (na >= C::NSA) na -= C::NSA;
+      const int nb = cb ^ 1;
+      pb.issue(ldsB + nb * C::kPanelB, k_begin + (kt + 1) * C::BK);
+      pa.issue(ldsA + na * C::kPanelA, k_begin + (kt + 2) * C::BK);
     }
-    const char* a_panel = smem + cur * C::kStage;
-    const char* b_panel = a_panel + C::kPanelA;
+    const char* a_panel = smem + ca * C::kPanelA;
+    const char* b_panel = smemB + cb * C::kPanelB;
     bf16x8 a[C::kKK][C::TA], b[C::kKK][C::TB];
 #pragma unroll
     for (int kk = 0; kk < C::kKK; ++kk) {
@@ -291,7 +260,7 @@ __device__ __forceinline__ void gemm_mainloop_pp(f32x16 (&acc)[C::TA][C::TB], co
       for (int u = 0; u < C::TB; ++u) b[kk][u] = pb.frag(b_panel, u, kk);
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    if (group == 1) wait_vmcnt<(C::NS - 2) * LPW>();   // group 1 reaches the barrier that opens stage kt+1 right after this phase
+    if (group == 1) wait_vmcnt<kAhead>();      // group 1 reaches the barrier that opens step kt + 1 right after this phase
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
@@ -305,11 +274,12 @@ __device__ __forceinline__ void gemm_mainloop_pp(f32x16 (&acc)[C::TA][C::TB], co
         for (int u = 0; u < C::TB; ++u)
           acc[t][u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk][t], b[kk][u], acc[t][u], 0, 0, 0);
     __builtin_amdgcn_s_setprio(0);
-    if (group == 0) wait_vmcnt<(C::NS - 2) * LPW>();   // group 0 opens stage kt+1 right after this phase
+    if (group == 0) wait_vmcnt<kAhead>();      // group 0 opens step kt + 1 right after this phase
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    cur = cur + 1 == C::NS ? 0 : cur + 1;
+    ca = ca + 1 == C::NSA ? 0 : ca + 1;
+    cb ^= 1;
   }
   if (group == 0) __builtin_amdgcn_s_barrier();
   wait_vmcnt<0>();

@@ -20,7 +20,7 @@
 
 namespace mst {
 
-// tile configuration of all four GEMMs: 2 x 4 waves, 4 x 2 MFMA tiles per wave, K step 64, 2 LDS stages
+// tile configuration of all four GEMMs: 2 x 4 waves, 4 x 2 MFMA tiles per wave, K step 64, LDS stages 3 (A) + 2 (B)
 typedef Cfg<2, 4, 4, 2, 64, 2> Tile;
 // same wave grid, half as wide on the B side: 256 x 128 block tile, wave tile 128 x 32
 typedef Cfg<2, 4, 4, 1, 64, 2> TileHalfB;
