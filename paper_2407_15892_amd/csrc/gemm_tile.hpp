@@ -50,7 +50,11 @@ struct Cfg {
   // LDS stages per operand: the B operand has NS, the A operand one more (its loads are issued one K step earlier)
   static constexpr int NSA = NS + 1, NSB = NS;
   static constexpr int kLds = NSA * kPanelA + NSB * kPanelB;
-  static constexpr int kKK = BK / 16;
+  static constexpr int kKK = BK / 16;            // MFMA k sub-steps per stage
+  typedef f32x16 Acc;                            // accumulator of one 32 x 32 MFMA tile
+  __device__ __forceinline__ static Acc mma(bf16x8 a, bf16x8 b, Acc c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+  }
 };
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
@@ -227,7 +231,7 @@ struct PanelKS {
 // Loads are always issued, also past the end of K: there they are out of range and write zeros into a stage
 // nobody reads.
 template <class C, class PA, class PB>
-__device__ __forceinline__ void gemm_mainloop_pp(f32x16 (&acc)[C::TA][C::TB], const PA& pa, const PB& pb,
+__device__ __forceinline__ void gemm_mainloop_pp(typename C::Acc (&acc)[C::TA][C::TB], const PA& pa, const PB& pb,
                                                  char* smem, int k_begin, int k_end, int group) {
   static_assert(C::NSA == 3 && C::NSB == 2, "three A stages, two B stages");
   constexpr int kAhead = PA::SPW;              // loads of one A stage per wave: allowed in flight at a wait
@@ -272,7 +276,7 @@ __device__ __forceinline__ void gemm_mainloop_pp(f32x16 (&acc)[C::TA][C::TB], co
       for (int t = 0; t < C::TA; ++t)
 #pragma unroll
         for (int u = 0; u < C::TB; ++u)
-          acc[t][u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk][t], b[kk][u], acc[t][u], 0, 0, 0);
+          acc[t][u] = C::mma(a[kk][t], b[kk][u], acc[t][u]);
     __builtin_amdgcn_s_setprio(0);
     if (group == 0) wait_vmcnt<kAhead>();      // group 0 opens step kt + 1 right after this phase
     __builtin_amdgcn_sched_barrier(0);

@@ -17,10 +17,17 @@
 // the tile space: workgroups that share an operand panel then share an L2.
 #pragma once
 #include "gemm_tile.hpp"
+#include "gemm_tile16.hpp"
 
 namespace mst {
 
-// tile configuration of all four GEMMs: 2 x 4 waves, 4 x 2 MFMA tiles per wave, K step 64, LDS stages 3 (A) + 2 (B)
+// tile configurations: 2 x 4 waves, wave tile 128 x 64, K step 64, LDS stages 3 (A) + 2 (B).
+//   Tile16: 8 x 4 tiles of v_mfma_f32_16x16x32_bf16 per wave -- the three logits-shaped GEMMs
+//   Tile:   4 x 2 tiles of v_mfma_f32_32x32x16_bf16 per wave -- the dW pass, whose fp32 read-modify-write of the
+//           output tile is better served by 32 lanes (128 bytes) per row than by 16
+typedef Cfg16<2, 4, 8, 4, 64, 2> Tile16;
+constexpr int kTA16 = Tile16::TA, kTB16 = Tile16::TB;
+static_assert(Tile16::EA == 256 && Tile16::EB == 256 && Tile16::kLds == 5 * 32768, "same block tile, same LDS");
 typedef Cfg<2, 4, 4, 2, 64, 2> Tile;
 // same wave grid, half as wide on the B side: 256 x 128 block tile, wave tile 128 x 32
 typedef Cfg<2, 4, 4, 1, 64, 2> TileHalfB;
@@ -163,8 +170,8 @@ __global__ __launch_bounds__(256) void k_shift_labels(const int* __restrict__ in
 // ---------------------------------------------------------------------------
 // forward: logits tile + running log-sum-exp partials + target logit
 //   A side = vocabulary (W rows), B side = chunk rows (H rows): a lane owns one
-//   row s and 16 consecutive vocabulary entries per MFMA tile, so the row
-//   reduction is in-lane plus one exchange with lane ^ 32.
+//   row s and 32 consecutive vocabulary entries, so the row reduction is in-lane
+//   plus exchanges with the other three lane quarters and the other wave row.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void k_fwd_gemm_lse(
     const __bf16* __restrict__ Hc, const __bf16* __restrict__ W, const int* __restrict__ labels_c,
@@ -179,76 +186,84 @@ __global__ __launch_bounds__(kThreads) void k_fwd_gemm_lse(
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wa = wave >> 2, wb = wave & 3;
 
-  f32x16 acc[kTA][kTB];
-  zero_acc<kTA, kTB>(acc);
-  PanelKC<Tile, kTile, kTA, true> pa;
-  PanelKC<Tile, kTile, kTB, false> pb;
+  f32x4 acc[kTA16][kTB16];
+  zero_acc<kTA16, kTB16>(acc);
+  PanelKC16<Tile16, kTile, kTA16, true> pa;
+  PanelKC16<Tile16, kTile, kTB16, false> pb;
   pa.init(W + (size_t)v0 * d, d, V - v0, d, wave, lane, wa);
   pb.init(Hc + (size_t)s0 * d, d, rows - s0, d, wave, lane, wb);
-  gemm_mainloop_pp<Tile>(acc, pa, pb, smem, 0, d, wa);
+  gemm_mainloop_pp<Tile16>(acc, pa, pb, smem, 0, d, wa);
 
-  const int va = v0 + wa * 128 + 16 * (lane >> 5);   // first vocabulary index of this lane in MFMA tile 0
+  // a lane (quarter g, column c) holds, for each of its 4 rows s, the 32 consecutive vocabulary entries
+  // va + 4 t + r (t = 0..7, r = 0..3)
+  const int g = lane >> 4, c = lane & 15;
+  const int va = v0 + wa * 128 + 32 * g;
   if (v0 + kTile > V) {                              // ragged last vocabulary tile: mask entries >= V
 #pragma unroll
-    for (int t = 0; t < kTA; ++t)
+    for (int t = 0; t < kTA16; ++t)
 #pragma unroll
-      for (int r = 0; r < 16; ++r)
-        if (va + 32 * t + r >= V) {
+      for (int r = 0; r < 4; ++r)
+        if (va + 4 * t + r >= V) {
 #pragma unroll
-          for (int u = 0; u < kTB; ++u) acc[t][u][r] = kMasked;
+          for (int u = 0; u < kTB16; ++u) acc[t][u][r] = kMasked;
         }
   }
 
-  float2* xch = reinterpret_cast<float2*>(smem);     // [wb][u][32] pairs from the wa == 1 waves
-  float m_u[kTB], l_u[kTB];
+  float2* xch = reinterpret_cast<float2*>(smem);     // [wb][u][16] pairs from the wa == 1 waves
+  float m_u[kTB16], l_u[kTB16];
 #pragma unroll
-  for (int u = 0; u < kTB; ++u) {
+  for (int u = 0; u < kTB16; ++u) {
     float m = kMasked;
 #pragma unroll
-    for (int t = 0; t < kTA; ++t)
+    for (int t = 0; t < kTA16; ++t)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) m = fmaxf(m, acc[t][u][r]);
+      for (int r = 0; r < 4; ++r) m = fmaxf(m, acc[t][u][r]);
     float l = 0.f;
     // subtract before scaling: with the masking sentinel, a fused (z * log2e - m * log2e)
     // would leave a huge rounding residue when z == m == sentinel
 #pragma unroll
-    for (int t = 0; t < kTA; ++t)
+    for (int t = 0; t < kTA16; ++t)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) l += fast_exp2((acc[t][u][r] - m) * kLog2e);
-    const float m2 = __shfl_xor(m, 32), l2 = __shfl_xor(l, 32);
-    const float mm = fmaxf(m, m2);
-    l = l * fast_exp2((m - mm) * kLog2e) + l2 * fast_exp2((m2 - mm) * kLog2e);
-    m_u[u] = mm;
+      for (int r = 0; r < 4; ++r) l += fast_exp2((acc[t][u][r] - m) * kLog2e);
+    // the four lane quarters hold four 32-entry slices of the same rows
+#pragma unroll
+    for (int o = 16; o <= 32; o <<= 1) {
+      const float m2 = __shfl_xor(m, o), l2 = __shfl_xor(l, o);
+      const float mm = fmaxf(m, m2);
+      l = l * fast_exp2((m - mm) * kLog2e) + l2 * fast_exp2((m2 - mm) * kLog2e);
+      m = mm;
+    }
+    m_u[u] = m;
     l_u[u] = l;
 
     // target logit straight from the accumulator that holds it
-    const int s_local = s0 + wb * 64 + 32 * u + (lane & 31);
+    const int s_local = s0 + wb * 64 + 16 * u + c;
     const int y = s_local < rows ? labels_c[s_local] : -1;
     const int rel = y - (v0 + wa * 128);
-    if (rel >= 0 && rel < 128 && y < V && ((rel >> 4) & 1) == (lane >> 5)) {
-      const int t_sel = rel >> 5, r_sel = rel & 15;
+    if (rel >= 0 && rel < 128 && y < V && (rel >> 5) == g) {
+      const int t_sel = (rel & 31) >> 2, r_sel = rel & 3;
       float val = 0.f;
 #pragma unroll
-      for (int t = 0; t < kTA; ++t)
+      for (int t = 0; t < kTA16; ++t)
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
+        for (int r = 0; r < 4; ++r)
           if (t == t_sel && r == r_sel) val = acc[t][u][r];
       tgt[s_local] = val;
     }
   }
   // the main loop ended with a barrier, LDS is free
-  if (wa == 1 && lane < 32) {
+  if (wa == 1 && lane < 16) {
 #pragma unroll
-    for (int u = 0; u < kTB; ++u) xch[(wb * kTB + u) * 32 + lane] = make_float2(m_u[u], l_u[u]);
+    for (int u = 0; u < kTB16; ++u) xch[(wb * kTB16 + u) * 16 + lane] = make_float2(m_u[u], l_u[u]);
   }
   __syncthreads();
-  if (wa == 0 && lane < 32) {
+  if (wa == 0 && lane < 16) {
 #pragma unroll
-    for (int u = 0; u < kTB; ++u) {
-      const float2 o = xch[(wb * kTB + u) * 32 + lane];
+    for (int u = 0; u < kTB16; ++u) {
+      const float2 o = xch[(wb * kTB16 + u) * 16 + lane];
       const float mm = fmaxf(m_u[u], o.x);
       const float l = l_u[u] * fast_exp2((m_u[u] - mm) * kLog2e) + o.y * fast_exp2((o.x - mm) * kLog2e);
-      const int s_local = s0 + wb * 64 + 32 * u + lane;
+      const int s_local = s0 + wb * 64 + 16 * u + lane;
       if (s_local < rows) part[(size_t)vt * part_stride + s_local] = make_float2(mm, l);
     }
   }
@@ -334,37 +349,35 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dlogits(
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wa = wave >> 2, wb = wave & 3;
 
-  f32x16 acc[kTA][kTB];
-  zero_acc<kTA, kTB>(acc);
-  PanelKC<Tile, kTile, kTA, true> pa;
-  PanelKC<Tile, kTile, kTB, false> pb;
+  f32x4 acc[kTA16][kTB16];
+  zero_acc<kTA16, kTB16>(acc);
+  PanelKC16<Tile16, kTile, kTA16, true> pa;
+  PanelKC16<Tile16, kTile, kTB16, false> pb;
   pa.init(W + (size_t)v0 * d, d, V - v0, d, wave, lane, wa);
   pb.init(Hc + (size_t)s0 * d, d, rows - s0, d, wave, lane, wb);
-  gemm_mainloop_pp<Tile>(acc, pa, pb, smem, 0, d, wa);
+  gemm_mainloop_pp<Tile16>(acc, pa, pb, smem, 0, d, wa);
 
-  const int va = v0 + wa * 128 + 16 * (lane >> 5);
+  const int va = v0 + wa * 128 + 32 * (lane >> 4);   // this lane's 32 consecutive vocabulary entries start here
 #pragma unroll
-  for (int u = 0; u < kTB; ++u) {
-    const int s_local = s0 + wb * 64 + 32 * u + (lane & 31);
+  for (int u = 0; u < kTB16; ++u) {
+    const int s_local = s0 + wb * 64 + 16 * u + (lane & 15);
     if (s_local >= rows) continue;
     const int y = labels_c[s_local];
     const bool valid = (y != ignore_index) && ((unsigned)y < (unsigned)V);
     const float lb = lse_c[s_local] * kLog2e;
     __bf16* grow = G + (size_t)s_local * ldg;
 #pragma unroll
-    for (int t = 0; t < kTA; ++t) {
-      const int vb = va + 32 * t;
-      bf16x8 lo, hi;
+    for (int p = 0; p < kTA16 / 2; ++p) {            // tiles 2p and 2p + 1: entries va + 8p .. + 7
+      bf16x8 o;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int v = vb + r;
-        float g = fast_exp2(acc[t][u][r] * kLog2e - lb);
-        if (v == y) g -= 1.0f;
-        if (!valid || v >= V) g = 0.f;
-        if (r < 8) lo[r] = (__bf16)g; else hi[r - 8] = (__bf16)g;
+      for (int e = 0; e < 8; ++e) {
+        const int v = va + 8 * p + e;
+        float gval = fast_exp2(acc[2 * p + (e >> 2)][u][e & 3] * kLog2e - lb);
+        if (v == y) gval -= 1.0f;
+        if (!valid || v >= V) gval = 0.f;
+        o[e] = (__bf16)gval;
       }
-      if (vb < ldg) *reinterpret_cast<bf16x8*>(grow + vb) = lo;
-      if (vb + 8 < ldg) *reinterpret_cast<bf16x8*>(grow + vb + 8) = hi;
+      if (va + 8 * p < ldg) *reinterpret_cast<bf16x8*>(grow + va + 8 * p) = o;
     }
   }
 }
@@ -393,22 +406,22 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dh(
   int k_end = k_begin + ksteps_per_split * kBK;
   if (k_end > V) k_end = V;
 
-  f32x16 acc[kTA][kTB];
-  zero_acc<kTA, kTB>(acc);
-  PanelKC<Tile, kTile, kTA, false> pa;
-  PanelKS<Tile, kTile, kTB> pb;
+  f32x4 acc[kTA16][kTB16];
+  zero_acc<kTA16, kTB16>(acc);
+  PanelKC16<Tile16, kTile, kTA16, false> pa;
+  PanelKS16<Tile16, kTile, kTB16> pb;
   pa.init(G + (size_t)s0 * ldg, ldg, rows - s0, ldg, wave, lane, wa);
   pb.init(W + j0, d, V, d - j0, wave, lane, wb);
-  gemm_mainloop_pp<Tile>(acc, pa, pb, smem, k_begin, k_end, wa);
+  gemm_mainloop_pp<Tile16>(acc, pa, pb, smem, k_begin, k_end, wa);
 
 #pragma unroll
-  for (int t = 0; t < kTA; ++t)
+  for (int t = 0; t < kTA16; ++t)
 #pragma unroll
-    for (int u = 0; u < kTB; ++u) {
-      const int j = j0 + wb * 64 + 32 * u + (lane & 31);
+    for (int u = 0; u < kTB16; ++u) {
+      const int j = j0 + wb * 64 + 16 * u + (lane & 15);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int s_local = s0 + wa * 128 + 32 * t + a_index_in_tile<false>(r, lane);
+      for (int r = 0; r < 4; ++r) {
+        const int s_local = s0 + wa * 128 + a_index_in_block16<false>(t, r, lane);
         if (s_local < rows && j < d) {
           if (n_split > 1) partial[((size_t)sp * rows_stride + s_local) * d + j] = acc[t][u][r];
           else dHc[(size_t)s_local * d + j] = (__bf16)(gamma_of(n_valid, grad_loss) * acc[t][u][r]);
