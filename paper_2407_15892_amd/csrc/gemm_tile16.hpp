@@ -123,6 +123,11 @@ struct PanelKS16 {
   uint32_t ok_mask, ld_bytes, slot0;
   uint32_t rd[TILES];
 
+  // XOR swizzle of the 16-byte chunk index by the k row.  A quarter wave reads 4 k rows x 4 pieces of 8 bytes.
+  // In memory order the 4 pieces of a row are 32 contiguous bytes (2 chunks), so rows must differ in chunk
+  // bits 1-2; with the permutation the pieces are 64 bytes (4 chunks) apart, so rows must differ in bits 0-1.
+  __device__ __forceinline__ static uint32_t swz(uint32_t krow) { return kPermute ? (krow & 3) : 2 * (krow & 3); }
+
   __device__ __forceinline__ void init(const void* base, uint32_t ld_elems, uint32_t k_rows, uint32_t cols_valid,
                                        int wave, int lane, int wave_side_index) {
     ld_bytes = ld_elems * 2;
@@ -133,7 +138,7 @@ struct PanelKS16 {
 #pragma unroll
     for (int i = 0; i < SPW; ++i) {
       const uint32_t krow = RPS * (slot0 + i) + lane / CPR;
-      const uint32_t chunk = (lane % CPR) ^ (2 * (krow & 3));
+      const uint32_t chunk = (lane % CPR) ^ swz(krow);
       voff[i] = krow * ld_bytes + chunk * 16;
       ok_mask |= ((chunk * 8) < cols_valid ? 1u : 0u) << i;
     }
@@ -143,7 +148,7 @@ struct PanelKS16 {
       const int col = kPermute ? wave_side_index * 128 + 32 * q + 4 * t
                                : wave_side_index * (16 * TILES) + 16 * t + 4 * q;
       const int krow = 8 * g + (i16 >> 2);
-      rd[t] = krow * RB + (((col >> 3) ^ (2 * (i16 >> 2))) * 16) + (col & 7) * 2;
+      rd[t] = krow * RB + (((col >> 3) ^ swz(krow)) * 16) + (col & 7) * 2;
     }
   }
   __device__ __forceinline__ void issue(uint32_t panel_lds, uint32_t k0) const {

@@ -30,7 +30,7 @@ constexpr int kTA16 = Tile16::TA, kTB16 = Tile16::TB;
 static_assert(Tile16::EA == 256 && Tile16::EB == 256 && Tile16::kLds == 5 * 32768, "same block tile, same LDS");
 typedef Cfg<2, 4, 4, 2, 64, 2> Tile;
 // same wave grid, half as wide on the B side: 256 x 128 block tile, wave tile 128 x 32
-typedef Cfg<2, 4, 4, 1, 64, 2> TileHalfB;
+typedef Cfg16<2, 4, 8, 2, 64, 2> Tile16HalfB;
 constexpr int kTile = 256;             // Tile::EA == Tile::EB
 constexpr int kBK = Tile::BK;
 constexpr int kThreads = Tile::kThreads;

@@ -55,8 +55,8 @@ void set_kernel_attributes() {
   set((const void*)k_mlp_gateup<false>);
   set((const void*)k_mlp_gateup<true>);
   set((const void*)k_mlp_gemm_nt);
-  set((const void*)k_mlp_gemm_nn<Tile>);
-  set((const void*)k_mlp_gemm_nn<TileHalfB>);
+  set((const void*)k_mlp_gemm_nn<Tile16>);
+  set((const void*)k_mlp_gemm_nn<Tile16HalfB>);
   set((const void*)k_mlp_dw3);
 }
 
@@ -98,12 +98,12 @@ void launch_nn(hipStream_t st, const __bf16* P1, const __bf16* Q1, const __bf16*
   const Tail tl = tail_split(n_nt, n_st);
   const int nt_full = n_nt - tl.a_tail;        // only a split of the A side (columns of Q) is used here
   const int n_full = tl.a_tail ? nt_full * kTile : N;
-  hipLaunchKernelGGL(k_mlp_gemm_nn<Tile>, dim3(xcd_grid_super(nt_full, n_st)), dim3(kThreads), kLdsBytes, st,
+  hipLaunchKernelGGL(k_mlp_gemm_nn<Tile16>, dim3(xcd_grid_super(nt_full, n_st)), dim3(kThreads), kLdsBytes, st,
                      P1, Q1, P2, Q2, ldp, ldq, rows, n_full, K, n_st, nt_full, out, ldo);
   if (tl.a_tail) {
-    const int n_sh = (rows + TileHalfB::EB - 1) / TileHalfB::EB;
-    hipLaunchKernelGGL(k_mlp_gemm_nn<TileHalfB>, dim3(xcd_grid_super(tl.a_tail, n_sh)), dim3(kThreads),
-                       TileHalfB::kLds, st, P1, Q1 + n_full, P2, Q2 ? Q2 + n_full : Q2, ldp, ldq, rows, N - n_full, K,
+    const int n_sh = (rows + Tile16HalfB::EB - 1) / Tile16HalfB::EB;
+    hipLaunchKernelGGL(k_mlp_gemm_nn<Tile16HalfB>, dim3(xcd_grid_super(tl.a_tail, n_sh)), dim3(kThreads),
+                       Tile16HalfB::kLds, st, P1, Q1 + n_full, P2, Q2 ? Q2 + n_full : Q2, ldp, ldq, rows, N - n_full, K,
                        n_sh, tl.a_tail, out + n_full, ldo);
   }
 }

@@ -45,9 +45,9 @@ __device__ __forceinline__ float sigmoid_f(float g) { return fast_rcp(1.0f + fas
 // ---------------------------------------------------------------------------
 // gate / up projections of a chunk with the SwiGLU epilogue.
 //   A side = intermediate index i, 128 per workgroup: the 256-row A panel holds, for each of the two
-//   wave rows, 64 gate rows (MFMA tiles 0, 1) and the 64 up rows of the same i (tiles 2, 3), so gate and
-//   up values of one (token, i) sit in the same lane and register of accumulators t and t + 2.
-//   B side = chunk rows (tokens).  A lane owns one token and 16 consecutive i per tile: 32-byte stores.
+//   wave rows, 64 gate rows (MFMA tiles 0..3) and the 64 up rows of the same i (tiles 4..7), so gate and
+//   up values of one (token, i) sit in the same lane and register of accumulators t and t + 4.
+//   B side = chunk rows (tokens).  A lane owns 4 tokens and 16 consecutive i for each: 32-byte stores.
 //   kBackward: dAG holds dA on entry and receives dG (same element, same lane); dU and A are written.
 // ---------------------------------------------------------------------------
 constexpr int kGateUpI = 128;   // intermediate indices per workgroup
@@ -64,67 +64,89 @@ __global__ __launch_bounds__(kThreads) void k_mlp_gateup(
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wa = wave >> 2, wb = wave & 3;
 
-  f32x16 acc[kTA][kTB];
-  zero_acc<kTA, kTB>(acc);
-  PanelKC<Tile, kTile, kTA, true> pa;
-  PanelKC<Tile, kTile, kTB, false> pb;
+  f32x4 acc[kTA16][kTB16];
+  zero_acc<kTA16, kTB16>(acc);
+  PanelKC16<Tile16, kTile, kTA16, true> pa;
+  PanelKC16<Tile16, kTile, kTB16, false> pb;
   {
-    // as a loader, wave w brings in MFMA tile w of the A panel: wave row w / 4, tile w % 4 of that row
-    const int t_l = wave & 3;
-    const int ib = i0 + 64 * (wave >> 2) + 32 * (t_l & 1);
-    const __bf16* src = (t_l < 2 ? Wg : Wu) + (size_t)ib * d;
-    pa.init_tile32(src, d, I - ib, d, wave, lane, wa);
+    // A panel, per wave row of 128 LDS rows: MFMA tiles 0..3 are gate rows, tiles 4..7 the up rows of the same 64
+    // intermediate indices; LDS row 16 t + 4 g + r holds index 16 g + 4 (t % 4) + r, so that a lane's gate value
+    // acc[t][u][r] and up value acc[t + 4][u][r] belong to the same index and its 16 indices are consecutive.
+    // As a loader, wave w fills LDS rows 32 w .. 32 w + 31 (tiles 2 (w % 4), 2 (w % 4) + 1 of wave row w / 4).
+    const int q = wave & 3;
+    const int ib = i0 + 64 * (wave >> 2);                       // first index of the loader's wave row
+    const __bf16* src = (q < 2 ? Wg : Wu) + (size_t)ib * d;
+    int valid = I - ib;
+    if (valid > 64) valid = 64;
+    pa.init_map(src, d, valid, d, wave, lane, wa,
+                [](int lrow) { const int m = lrow & 127; return 16 * ((m >> 2) & 3) + 4 * ((m >> 4) & 3) + (m & 3); }, false);
   }
   pb.init(Xc + (size_t)s0 * d, d, rows - s0, d, wave, lane, wb);
-  gemm_mainloop_pp<Tile>(acc, pa, pb, smem, 0, d, wa);
+  gemm_mainloop_pp<Tile16>(acc, pa, pb, smem, 0, d, wa);
 
+  const int ib = i0 + 64 * wa + 16 * (lane >> 4);              // this lane's 16 consecutive intermediate indices
 #pragma unroll
-  for (int u = 0; u < kTB; ++u) {
-    const int s_local = s0 + wb * 64 + 32 * u + (lane & 31);
+  for (int u = 0; u < kTB16; ++u) {
+    const int s_local = s0 + wb * 64 + 16 * u + (lane & 15);
+    if (s_local >= rows || ib >= I) continue;                  // I % 8 == 0: a group of 8 is inside or outside
+    const size_t off = (size_t)s_local * I + ib;
+    const bool hi_ok = ib + 8 < I;
+    bf16x8 da[2];
+    if (kBackward) {
+      da[0] = *reinterpret_cast<const bf16x8*>(dAG + off);
+      if (hi_ok) da[1] = *reinterpret_cast<const bf16x8*>(dAG + off + 8);
+    }
+    bf16x8 a_o[2], g_o[2], u_o[2];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {                             // index ib + e: tile e / 4, register e % 4
+      const float g = acc[e >> 2][u][e & 3], up = acc[4 + (e >> 2)][u][e & 3];
+      const float sg = sigmoid_f(g);
+      const float act = g * sg;                                // silu(g)
+      a_o[e >> 3][e & 7] = (__bf16)(act * up);
+      if (kBackward) {
+        const float dav = (float)da[e >> 3][e & 7];
+        g_o[e >> 3][e & 7] = (__bf16)(dav * up * (sg * (1.0f + g * (1.0f - sg))));   // dA * U * silu'(G)
+        u_o[e >> 3][e & 7] = (__bf16)(dav * act);                                    // dA * silu(G)
+      }
+    }
+    *reinterpret_cast<bf16x8*>(A + off) = a_o[0];
+    if (hi_ok) *reinterpret_cast<bf16x8*>(A + off + 8) = a_o[1];
+    if (kBackward) {
+      *reinterpret_cast<bf16x8*>(dAG + off) = g_o[0];
+      *reinterpret_cast<bf16x8*>(dU + off) = u_o[0];
+      if (hi_ok) {
+        *reinterpret_cast<bf16x8*>(dAG + off + 8) = g_o[1];
+        *reinterpret_cast<bf16x8*>(dU + off + 8) = u_o[1];
+      }
+    }
+  }
+}
+
+// epilogue of the two plain GEMMs: a lane holds, for each of its rows s, 32 consecutive n (A side, permuted):
+// four 16-byte bf16 stores per row
+template <class T>
+__device__ __forceinline__ void store_rows_bf16(const f32x4 (&acc)[T::TA][T::TB], __bf16* __restrict__ out, int ldo,
+                                                int rows, int N, int s0, int n0, int wa, int wb, int lane) {
+  static_assert(T::TA == 8, "one 128-wide permuted block per wave row");
+  const int nb = n0 + wa * 128 + 32 * (lane >> 4);
+#pragma unroll
+  for (int u = 0; u < T::TB; ++u) {
+    const int s_local = s0 + wb * (16 * T::TB) + 16 * u + (lane & 15);
     if (s_local >= rows) continue;
-    const size_t row_off = (size_t)s_local * I;
+    __bf16* orow = out + (size_t)s_local * ldo;
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const int ib = i0 + 64 * wa + 32 * t + 16 * (lane >> 5);
-      if (ib >= I) continue;                       // I % 8 == 0: a group of 8 is inside or outside
-      const bool hi_ok = ib + 8 < I;
-      bf16x8 da_lo, da_hi;
-      if (kBackward) {
-        da_lo = *reinterpret_cast<const bf16x8*>(dAG + row_off + ib);
-        if (hi_ok) da_hi = *reinterpret_cast<const bf16x8*>(dAG + row_off + ib + 8);
-      }
-      bf16x8 a_lo, a_hi, g_lo, g_hi, u_lo, u_hi;
+    for (int p = 0; p < 4; ++p) {                    // tiles 2p and 2p + 1: n = nb + 8p .. + 7
+      bf16x8 o;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float g = acc[t][u][r], up = acc[t + 2][u][r];
-        const float s = sigmoid_f(g);
-        const float act = g * s;                                   // silu(g)
-        const float a = act * up;
-        if (r < 8) a_lo[r] = (__bf16)a; else a_hi[r - 8] = (__bf16)a;
-        if (kBackward) {
-          const float da = (float)(r < 8 ? da_lo[r] : da_hi[r - 8]);
-          const float dg = da * up * (s * (1.0f + g * (1.0f - s)));  // dA * U * silu'(G)
-          const float du = da * act;                                 // dA * silu(G)
-          if (r < 8) { g_lo[r] = (__bf16)dg; u_lo[r] = (__bf16)du; } else { g_hi[r - 8] = (__bf16)dg; u_hi[r - 8] = (__bf16)du; }
-        }
-      }
-      *reinterpret_cast<bf16x8*>(A + row_off + ib) = a_lo;
-      if (hi_ok) *reinterpret_cast<bf16x8*>(A + row_off + ib + 8) = a_hi;
-      if (kBackward) {
-        *reinterpret_cast<bf16x8*>(dAG + row_off + ib) = g_lo;
-        *reinterpret_cast<bf16x8*>(dU + row_off + ib) = u_lo;
-        if (hi_ok) {
-          *reinterpret_cast<bf16x8*>(dAG + row_off + ib + 8) = g_hi;
-          *reinterpret_cast<bf16x8*>(dU + row_off + ib + 8) = u_hi;
-        }
-      }
+      for (int e = 0; e < 8; ++e) o[e] = (__bf16)acc[2 * p + (e >> 2)][u][e & 3];
+      if (nb + 8 * p < N) *reinterpret_cast<bf16x8*>(orow + nb + 8 * p) = o;      // N % 8 == 0
     }
   }
 }
 
 // ---------------------------------------------------------------------------
 // out[s][n] = sum_k P[s][k] Q[n][k]      (both operands K-contiguous; used for O_chunk = A Wd^T)
-//   A side = n (rows of Q, permuted so a lane holds 16 consecutive n), B side = s (rows of P)
+//   A side = n (rows of Q, permuted so a lane holds 32 consecutive n), B side = s (rows of P)
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void k_mlp_gemm_nt(
     const __bf16* __restrict__ P, int ldp, const __bf16* __restrict__ Q, int ldq, int rows, int N, int K,
@@ -137,38 +159,21 @@ __global__ __launch_bounds__(kThreads) void k_mlp_gemm_nt(
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wa = wave >> 2, wb = wave & 3;
 
-  f32x16 acc[kTA][kTB];
-  zero_acc<kTA, kTB>(acc);
-  PanelKC<Tile, kTile, kTA, true> pa;
-  PanelKC<Tile, kTile, kTB, false> pb;
+  f32x4 acc[kTA16][kTB16];
+  zero_acc<kTA16, kTB16>(acc);
+  PanelKC16<Tile16, kTile, kTA16, true> pa;
+  PanelKC16<Tile16, kTile, kTB16, false> pb;
   pa.init(Q + (size_t)n0 * ldq, ldq, N - n0, K, wave, lane, wa);
   pb.init(P + (size_t)s0 * ldp, ldp, rows - s0, K, wave, lane, wb);
-  gemm_mainloop_pp<Tile>(acc, pa, pb, smem, 0, K, wa);
-
-#pragma unroll
-  for (int u = 0; u < kTB; ++u) {
-    const int s_local = s0 + wb * 64 + 32 * u + (lane & 31);
-    if (s_local >= rows) continue;
-    __bf16* orow = out + (size_t)s_local * ldo;
-#pragma unroll
-    for (int t = 0; t < kTA; ++t) {
-      const int nb = n0 + wa * 128 + 32 * t + 16 * (lane >> 5);
-      bf16x8 lo, hi;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        if (r < 8) lo[r] = (__bf16)acc[t][u][r]; else hi[r - 8] = (__bf16)acc[t][u][r];
-      }
-      if (nb < N) *reinterpret_cast<bf16x8*>(orow + nb) = lo;          // N % 8 == 0
-      if (nb + 8 < N) *reinterpret_cast<bf16x8*>(orow + nb + 8) = hi;
-    }
-  }
+  gemm_mainloop_pp<Tile16>(acc, pa, pb, smem, 0, K, wa);
+  store_rows_bf16<Tile16>(acc, out, ldo, rows, N, s0, n0, wa, wb, lane);
 }
 
 // ---------------------------------------------------------------------------
 // out[s][n] = sum_k P1[s][k] Q1[k][n] (+ sum_k P2[s][k] Q2[k][n])   (Q K-strided)
 //   used for dA = dO Wd (one term, K = d) and dX = dG Wg + dU Wu (two terms, K = I each)
-//   A side = n (columns of Q, read transposed with the row permutation, so a lane holds 16 consecutive n
-//   and stores 32 bytes), B side = s (rows of P).  T: Tile, or TileHalfB for a partly filled last round.
+//   A side = n (columns of Q, read transposed with the row permutation, so a lane holds 32 consecutive n
+//   and stores 64 bytes), B side = s (rows of P).  T: Tile16, or Tile16HalfB for a partly filled last round.
 // ---------------------------------------------------------------------------
 template <class T>
 __global__ __launch_bounds__(kThreads) void k_mlp_gemm_nn(
@@ -183,40 +188,23 @@ __global__ __launch_bounds__(kThreads) void k_mlp_gemm_nn(
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wa = wave / T::WB, wb = wave % T::WB;
 
-  f32x16 acc[T::TA][T::TB];
+  f32x4 acc[T::TA][T::TB];
   zero_acc<T::TA, T::TB>(acc);
   {
-    PanelKS<T, T::EA, T::TA, true> pa;
-    PanelKC<T, T::EB, T::TB, false> pb;
+    PanelKS16<T, T::EA, T::TA, true> pa;
+    PanelKC16<T, T::EB, T::TB, false> pb;
     pa.init(Q1 + n0, ldq, K, N - n0, wave, lane, wa);
     pb.init(P1 + (size_t)s0 * ldp, ldp, rows - s0, K, wave, lane, wb);
     gemm_mainloop_pp<T>(acc, pa, pb, smem, 0, K, wa);
   }
   if (P2 != nullptr) {
-    PanelKS<T, T::EA, T::TA, true> pa;
-    PanelKC<T, T::EB, T::TB, false> pb;
+    PanelKS16<T, T::EA, T::TA, true> pa;
+    PanelKC16<T, T::EB, T::TB, false> pb;
     pa.init(Q2 + n0, ldq, K, N - n0, wave, lane, wa);
     pb.init(P2 + (size_t)s0 * ldp, ldp, rows - s0, K, wave, lane, wb);
     gemm_mainloop_pp<T>(acc, pa, pb, smem, 0, K, wa);
   }
-
-#pragma unroll
-  for (int u = 0; u < T::TB; ++u) {
-    const int s_local = s0 + wb * (32 * T::TB) + 32 * u + (lane & 31);
-    if (s_local >= rows) continue;
-    __bf16* orow = out + (size_t)s_local * ldo;
-#pragma unroll
-    for (int t = 0; t < T::TA; ++t) {
-      const int nb = n0 + wa * (32 * T::TA) + 32 * t + 16 * (lane >> 5);
-      bf16x8 lo, hi;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        if (r < 8) lo[r] = (__bf16)acc[t][u][r]; else hi[r - 8] = (__bf16)acc[t][u][r];
-      }
-      if (nb < N) *reinterpret_cast<bf16x8*>(orow + nb) = lo;          // N % 8 == 0
-      if (nb + 8 < N) *reinterpret_cast<bf16x8*>(orow + nb + 8) = hi;
-    }
-  }
+  store_rows_bf16<T>(acc, out, ldo, rows, N, s0, n0, wa, wb, lane);
 }
 
 // ---------------------------------------------------------------------------
