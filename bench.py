@@ -31,10 +31,10 @@ GEMM_KINDS = ("fwd_gemm_lse", "bwd_gemm_dlogits", "bwd_gemm_dh", "bwd_gemm_dw")
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command (see profiles/),
 # scaled by what the same counters read for a device copy of known size; keyed by (config, kernel kind).
 PMC_TRAFFIC_BYTES = {
-    (2, "fwd_gemm_lse"): 1.824e9 + 0.004e9,
-    (2, "bwd_gemm_dlogits"): 1.831e9 + 0.270e9,
-    (2, "bwd_gemm_dh"): 1.579e9 + 0.067e9,
-    (2, "bwd_gemm_dw"): 4.944e9 + 2.101e9,
+    (2, "fwd_gemm_lse"): 1.689e9 + 0.004e9,
+    (2, "bwd_gemm_dlogits"): 1.760e9 + 0.264e9,
+    (2, "bwd_gemm_dh"): 1.581e9 + 0.068e9,
+    (2, "bwd_gemm_dw"): 4.855e9 + 2.101e9,
 }
 
 
@@ -85,12 +85,12 @@ MLP_KINDS = ("gateup", "down", "da", "gateup_bwd", "dx", "dw")
 MLP_FLOP_UNITS = {"gateup": 4.0, "down": 2.0, "da": 2.0, "gateup_bwd": 4.0, "dx": 4.0, "dw": 6.0}
 # HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of `bench.py --path mlp` (see profiles/)
 MLP_PMC_TRAFFIC_BYTES = {
-    (2, "gateup"): 1.410e9 + 0.118e9,
+    (2, "gateup"): 1.409e9 + 0.117e9,
     (2, "down"): 0.705e9 + 0.035e9,
-    (2, "da"): 0.783e9 + 0.133e9,
-    (2, "gateup_bwd"): 1.534e9 + 0.473e9,
-    (2, "dx"): 1.413e9 + 0.039e9,
-    (2, "dw"): 3.376e9 + 0.705e9,
+    (2, "da"): 0.786e9 + 0.137e9,
+    (2, "gateup_bwd"): 1.527e9 + 0.353e9,
+    (2, "dx"): 1.414e9 + 0.040e9,
+    (2, "dw"): 3.252e9 + 0.705e9,
 }
 
 
