@@ -485,7 +485,7 @@ __device__ __forceinline__ void dw_tile(
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int v = v0 + wa * 128 + 32 * t + a_index_in_tile<false>(r, lane);
-          acc[t][u][r] = (v < V && j < d) ? dW[(size_t)v * ldw + j] : 0.f;
+          acc[t][u][r] = (v < V && j < d) ? __builtin_nontemporal_load(dW + (size_t)v * ldw + j) : 0.f;
         }
       }
   } else {
@@ -505,7 +505,7 @@ __device__ __forceinline__ void dw_tile(
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int v = v0 + wa * 128 + 32 * t + a_index_in_tile<false>(r, lane);
-        if (v < V && j < d) dW[(size_t)v * ldw + j] = scale * acc[t][u][r];
+        if (v < V && j < d) __builtin_nontemporal_store(scale * acc[t][u][r], dW + (size_t)v * ldw + j);
       }
     }
 }
