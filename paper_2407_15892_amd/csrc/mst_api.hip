@@ -55,17 +55,20 @@ mst_status make_plan(int64_t S, int64_t d, int64_t V, int32_t M, Plan* p) {
   p->n_vt = (int)((V + kTile - 1) / kTile);
   p->n_jt = (int)((d + kTile - 1) / kTile);
   p->n_st = (int)((C + kTile - 1) / kTile);
-  // dH: few output tiles, long contraction -> split V so that about one workgroup per CU exists
+  // dH: few output tiles, long contraction -> split V so that the workgroups fill whole rounds of kNumCu
+  // (one workgroup is resident per CU).  Among the split counts that fit (at most kMaxDhSplit, at most one per
+  // K step, partials must fit into the dlogits slot that is free at that moment) take the one with the fullest
+  // rounds, with a small penalty per split for the fp32 partials it adds.
   const int out_tiles = p->n_st * p->n_jt;
   const int ksteps = (int)((V + kBK - 1) / kBK);
-  int split = (kNumCu + out_tiles / 2) / out_tiles;
-  if (split < 1) split = 1;
-  if (split > kMaxDhSplit) split = kMaxDhSplit;
-  if (split > ksteps) split = ksteps;
-  // the split partials of one chunk live in the dlogits slot that is free at that moment
-  {
-    const int64_t room = (C * ldg * 2) / (C * d * 4);
-    if (split > 1 && (int64_t)split > room) split = room >= 2 ? (int)room : 1;
+  const int64_t room = (C * ldg * 2) / (C * d * 4);
+  int split = 1;
+  double best = -1.0;
+  for (int s = 1; s <= kMaxDhSplit && s <= ksteps && (s == 1 || s <= room); ++s) {
+    const int wgs = out_tiles * s;
+    const int rounds = (wgs + kNumCu - 1) / kNumCu;
+    const double score = (double)wgs / ((double)rounds * kNumCu) - 0.002 * s;
+    if (score > best) { best = score; split = s; }
   }
   p->dh_ksteps = (ksteps + split - 1) / split;
   p->dh_split = (ksteps + p->dh_ksteps - 1) / p->dh_ksteps;
