@@ -1,33 +1,28 @@
-// Block-tile bf16 GEMM main loop for gfx950 (MI355X), shared by the four
-// contractions of the mini-sequence LM-head path (Algorithm 2 line 4 and
-// Algorithm 4 lines 5, 7, 8 of the paper).
+// Block-tile bf16 GEMM main loop for gfx950 (MI355X), shared by the contractions of the mini-sequence
+// LM-head path (Algorithm 2 line 4 and Algorithm 4 lines 5, 7, 8 of the paper) and of the mini-sequence MLP
+// path (Algorithms 1 and 3).
 //
-// One workgroup of 512 threads (8 wave64s, two per SIMD) owns a 256 x 256
-// output tile.  Operand panels of 256 x 64 bf16 are brought from global memory
-// straight into LDS (buffer loads with the LDS bit, 16 bytes per lane, no
-// register staging), three stages deep for the A operand and two for the B
-// operand (all 160 KB of LDS), and consumed by v_mfma_f32_32x32x16_bf16.
-// The wave grid is 2 (A side) x 4 (B side): a wave accumulates 128 x 64, i.e.
-// 4 x 2 MFMA tiles = 128 fp32 accumulator registers per lane.
+// One workgroup of 512 threads (8 wave64s, two per SIMD) owns a 256 x 256 output tile.  Operand panels of
+// 256 x 64 bf16 are brought from global memory straight into LDS (buffer loads with the LDS bit, 16 bytes
+// per lane, no register staging), three stages deep for the A operand and two for the B operand (all 160 KB
+// of LDS), and consumed by MFMA instructions.  The wave grid is 2 (A side) x 4 (B side): a wave accumulates
+// 128 x 64 = 128 fp32 accumulator registers per lane.  This header holds the main loop and the panel classes
+// for v_mfma_f32_32x32x16_bf16 tiles (4 x 2 per wave, used by the weight-gradient passes); gemm_tile16.hpp
+// holds the panel classes for v_mfma_f32_16x16x32_bf16 tiles (8 x 4 per wave, used by everything else).
 //
-// The two halves of the workgroup (waves 0-3 and 4-7, one wave of each half on
-// every SIMD) run half a step apart: while one half reads its fragments of a
-// stage out of LDS and issues the global loads of a later stage, the other
-// half issues that stage's 32 MFMAs from registers; one workgroup barrier per
-// phase keeps them alternating, so the matrix pipe of a SIMD is fed by one
-// wave while its sibling waits on memory.
+// The two halves of the workgroup (waves 0-3 and 4-7, one wave of each half on every SIMD) run half a step
+// apart: while one half reads its fragments of a stage out of LDS and issues the global loads of later
+// stages, the other half issues that stage's MFMAs from registers; one workgroup barrier per phase keeps
+// them alternating, so the matrix pipe of a SIMD is fed by one wave while its sibling waits on memory.
 //
-// "A side" is the index that ends up spread over a lane's 16 accumulator
-// registers, "B side" the index that ends up across the 32 lanes of a half
-// wave.  Either operand may be stored K-contiguous (layout KC: X[index][k]) or
-// K-strided (layout KS: X[k][index]).  KC panels are read from LDS with
-// ds_read_b128; KS panels with the transposing ds_read_b64_tr_b16, so no
-// operand is ever transposed in memory.
+// "A side" is the index that ends up spread over a lane's accumulator registers, "B side" the index that
+// ends up across lanes.  Either operand may be stored K-contiguous (layout KC: X[index][k]) or K-strided
+// (layout KS: X[k][index]).  KC panels are read from LDS with ds_read_b128; KS panels with the transposing
+// ds_read_b64_tr_b16, so no operand is ever transposed in memory.
 //
-// Buffer resources give hardware range checking: a lane whose address lies
-// beyond the matrix reads zeros instead of faulting, which is how ragged tile
-// edges are handled without branches, and why loads may be issued past the
-// end of K (they write zeros into a stage nobody reads).
+// Buffer resources give hardware range checking: a lane whose address lies beyond the matrix reads zeros
+// instead of faulting, which is how ragged tile edges are handled without branches, and why loads may be
+// issued past the end of K (they write zeros into a stage nobody reads).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
