@@ -43,8 +43,8 @@
  *     causes an out-of-range access; the forward call then writes NaN to *loss
  *     and -1 to *n_valid.
  *   - Requirements: d % 8 == 0; H, W, dH 16-byte aligned; dW, lse 4-byte
- *     aligned; workspace 256-byte aligned; 1 <= M <= S; V * d < 2^31;
- *     ceil(S/M) * (V rounded up to 8) < 2^31.
+ *     aligned; workspace 256-byte aligned; 1 <= M <= S; d < 2^22;
+ *     V * d < 2^31; ceil(S/M) * (V rounded up to 8) < 2^30.
  *   - Arithmetic: bf16 operands, fp32 MFMA accumulation, fp32 log-sum-exp and
  *     softmax, dlogits = softmax - onehot rounded to bf16 (nearest even)
  *     before the two gradient GEMMs, grad_loss / N_valid applied in fp32 by

@@ -43,7 +43,7 @@
  *     host before anything is launched.
  *   - Requirements: d % 8 == 0, I % 8 == 0; X, Wg, Wu, Wd, dO, O, dX 16-byte
  *     aligned; dWg, dWu, dWd 4-byte aligned; workspace 256-byte aligned;
- *     1 <= M <= S; I * d < 2^31; ceil(S/M) * I < 2^30.
+ *     1 <= M <= S; d, I < 2^22; I * d < 2^31; ceil(S/M) * I < 2^30.
  *   - Arithmetic: bf16 operands, fp32 MFMA accumulation; silu, its derivative
  *     and the products in fp32 on the accumulators; A, dA, dG, dU rounded to
  *     bf16 (nearest even) before the GEMMs that consume them; O and dX

@@ -44,7 +44,7 @@ mst_status make_plan(int64_t S, int64_t d, int64_t V, int32_t M, Plan* p) {
   if (S <= 0 || d <= 0 || V <= 0) return MST_ERR_BAD_SHAPE;
   if (d % 8 != 0) return MST_ERR_BAD_SHAPE;
   if (M < 1 || (int64_t)M > S) return MST_ERR_BAD_M;
-  if (V * d >= (int64_t(1) << 31)) return MST_ERR_BAD_SHAPE;
+  if (V * d >= (int64_t(1) << 31) || d >= (int64_t(1) << 22)) return MST_ERR_BAD_SHAPE;
   const int64_t C = (S + M - 1) / M;
   const int64_t ldg = (V + 7) / 8 * 8;
   if (C * ldg >= (int64_t(1) << 30) || C * d >= (int64_t(1) << 30)) return MST_ERR_BAD_SHAPE;
@@ -150,7 +150,7 @@ const char* mst_strerror(mst_status s) {
   switch (s) {
     case MST_OK: return "ok";
     case MST_ERR_NULL_POINTER: return "a required pointer is NULL";
-    case MST_ERR_BAD_SHAPE: return "bad shape: S, d, V must be positive, d % 8 == 0, V*d < 2^31, ceil(S/M)*V < 2^31";
+    case MST_ERR_BAD_SHAPE: return "bad shape: S, d, V must be positive, d % 8 == 0, d < 2^22, V*d < 2^31, ceil(S/M)*V < 2^30";
     case MST_ERR_BAD_M: return "M must satisfy 1 <= M <= S";
     case MST_ERR_WORKSPACE: return "workspace is NULL or too small (see mst_workspace_bytes)";
     case MST_ERR_ALIGNMENT: return "pointer alignment: H, W, dH 16 bytes; workspace 256 bytes; lse, dW 4 bytes";

@@ -475,21 +475,35 @@ __device__ __forceinline__ void dw_tile(
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wa = wave >> 2, wb = wave & 3;
 
+  // The fp32 tile is read and written through a buffer descriptor that covers the tile's valid rows: one
+  // scalar-base instruction per element with a 32-bit offset, rows past V dropped by the hardware range
+  // check (loads of them return 0), columns past d masked per lane.  Both streams are non-temporal.
+  const int rows_valid = V - v0 < kTile ? V - v0 : kTile;
+  const __amdgpu_buffer_rsrc_t out = make_rsrc_uniform(dW + (size_t)v0 * ldw, (uint32_t)rows_valid * (uint32_t)ldw * 4u);
+  constexpr int kNonTemporal = 2;
+  uint32_t lane_off[kTB];
+  bool col_ok[kTB];
+#pragma unroll
+  for (int u = 0; u < kTB; ++u) {
+    const int j = j0 + wb * 64 + 32 * u + (lane & 31);
+    col_ok[u] = j < d;
+    lane_off[u] = ((uint32_t)(wa * 128 + 4 * (lane >> 5)) * (uint32_t)ldw + (uint32_t)j) * 4u;
+  }
+  // register r of accumulator tile t holds row 32 t + 8 (r / 4) + r % 4 (+ the lane part above)
+  auto row_off = [&](int t, int r) { return (uint32_t)(32 * t + 8 * (r >> 2) + (r & 3)) * (uint32_t)ldw * 4u; };
+
   f32x16 acc[kTA][kTB];
+  zero_acc<kTA, kTB>(acc);
   if (accumulate) {
 #pragma unroll
-    for (int t = 0; t < kTA; ++t)
+    for (int u = 0; u < kTB; ++u)
+      if (col_ok[u]) {
 #pragma unroll
-      for (int u = 0; u < kTB; ++u) {
-        const int j = j0 + wb * 64 + 32 * u + (lane & 31);
+        for (int t = 0; t < kTA; ++t)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int v = v0 + wa * 128 + 32 * t + a_index_in_tile<false>(r, lane);
-          acc[t][u][r] = (v < V && j < d) ? __builtin_nontemporal_load(dW + (size_t)v * ldw + j) : 0.f;
-        }
+          for (int r = 0; r < 16; ++r)
+            acc[t][u][r] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(out, lane_off[u] + row_off(t, r), 0, kNonTemporal));
       }
-  } else {
-    zero_acc<kTA, kTB>(acc);
   }
   PanelKS<Tile, kTile, kTA> pa;
   PanelKS<Tile, kTile, kTB> pb;
@@ -497,16 +511,19 @@ __device__ __forceinline__ void dw_tile(
   pb.init(Hc + j0, ldh, rows, d - j0, wave, lane, wb);
   gemm_mainloop_pp<Tile>(acc, pa, pb, smem, 0, rows, wa);
 
+  // scaled in place first: a store whose data sits in a reused temporary would have to wait for older stores
 #pragma unroll
   for (int t = 0; t < kTA; ++t)
 #pragma unroll
-    for (int u = 0; u < kTB; ++u) {
-      const int j = j0 + wb * 64 + 32 * u + (lane & 31);
+    for (int u = 0; u < kTB; ++u) acc[t][u] *= scale;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int v = v0 + wa * 128 + 32 * t + a_index_in_tile<false>(r, lane);
-        if (v < V && j < d) __builtin_nontemporal_store(scale * acc[t][u][r], dW + (size_t)v * ldw + j);
-      }
+  for (int u = 0; u < kTB; ++u)
+    if (col_ok[u]) {
+#pragma unroll
+      for (int t = 0; t < kTA; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[t][u][r]), out, lane_off[u] + row_off(t, r), 0, kNonTemporal);
     }
 }
 

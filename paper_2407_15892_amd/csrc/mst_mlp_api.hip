@@ -27,7 +27,7 @@ mst_status make_plan(int64_t S, int64_t d, int64_t I, int32_t M, Plan* p) {
   if (S <= 0 || d <= 0 || I <= 0) return MST_ERR_BAD_SHAPE;
   if (d % 8 != 0 || I % 8 != 0) return MST_ERR_BAD_SHAPE;
   if (M < 1 || (int64_t)M > S) return MST_ERR_BAD_M;
-  if (I * d >= (int64_t(1) << 31)) return MST_ERR_BAD_SHAPE;
+  if (I * d >= (int64_t(1) << 31) || d >= (int64_t(1) << 22) || I >= (int64_t(1) << 22)) return MST_ERR_BAD_SHAPE;
   const int64_t C = (S + M - 1) / M;
   if (C * I >= (int64_t(1) << 30) || C * d >= (int64_t(1) << 30)) return MST_ERR_BAD_SHAPE;
   p->S = S; p->d = d; p->I = I; p->M = M;
