@@ -504,6 +504,13 @@ __device__ __forceinline__ void dw_tile(
           for (int r = 0; r < 16; ++r)
             acc[t][u][r] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(out, lane_off[u] + row_off(t, r), 0, kNonTemporal));
       }
+    // The compiler has to see these loads complete before the main loop: its own wait-count bookkeeping
+    // cannot see the loop's hand-placed waits, so it would otherwise wait for every outstanding load
+    // (the operand prefetches included) in front of the first MFMAs of every K step.
+#pragma unroll
+    for (int t = 0; t < kTA; ++t)
+#pragma unroll
+      for (int u = 0; u < kTB; ++u) asm volatile("" : "+v"(acc[t][u]));
   }
   PanelKS<Tile, kTile, kTA> pa;
   PanelKS<Tile, kTile, kTB> pb;
