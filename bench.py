@@ -220,6 +220,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--cpu-sample-rows", type=int, default=4096)
+    ap.add_argument("--bwd-schedule", choices=("auto", "pairs", "blocks"), default="auto",
+                    help="order of the LM-head backward pass (default: the library's own choice)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="do not bracket kernels with events inside the timed region")
@@ -243,7 +245,11 @@ def main() -> int:
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         return 2
     mst.load_library()
+    mst.mst_set_bwd_schedule({"auto": mst.BWD_SCHEDULE_AUTO, "pairs": mst.BWD_SCHEDULE_PAIRS,
+                              "blocks": mst.BWD_SCHEDULE_BLOCKS}[args.bwd_schedule])
     cfg = mi.CONFIGS[args.config]
+    sched = mst.mst_bwd_schedule_info(cfg.S, cfg.d, cfg.V, cfg.M)
+    sched["schedule"] = {mst.BWD_SCHEDULE_PAIRS: "pairs", mst.BWD_SCHEDULE_BLOCKS: "blocks"}[sched["schedule"]]
     t0 = time.perf_counter()
     inp = mi.make_inputs(cfg)
     gen_s = time.perf_counter() - t0
@@ -320,9 +326,11 @@ def main() -> int:
                     "flop_per_launch": flop_per_launch(dom), "avg_launch_ms": ms / n,
                     "launches_per_step": n / args.steps}
         if dom == "bwd_gemm_dw":
-            # this kernel also moves dW through HBM once per launch (read + write, first launch write only)
+            # this kernel also moves dW through HBM: every row block writes it, every block after the first reads it
+            # first; dlogits is read once, H once per vocabulary window
             passes = n / args.steps
-            alg_bytes = (2 * passes - 1) / passes * 4.0 * V * d + 2.0 * (S / passes) * V + 2.0 * (S / passes) * d
+            n_rb, n_win = sched["row_blocks"], sched["windows"]
+            alg_bytes = ((2 * n_rb - 1) * 4.0 * V * d + 2.0 * S * V + 2.0 * S * d * n_win) / passes
             roofline["hbm_side"] = {"algorithmic_bytes_per_launch": alg_bytes,
                                     "achieved_GBs": alg_bytes / (ms / n * 1e-3) / 1e9, "peak_GBs": PEAK_HBM_GBS,
                                     "frac": alg_bytes / (ms / n * 1e-3) / 1e9 / PEAK_HBM_GBS}
@@ -343,7 +351,7 @@ def main() -> int:
         "tflops_6SdV_convention": 6.0 * S * d * V / (ms_per_step * 1e-3) / 1e12,
         "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
         "peak_workspace_bytes": {"fwd": fwd_bytes, "bwd": bwd_bytes, "cap_one_fp32_logits_chunk": cfg.C * V * 4},
-        "loss": float(loss.item()), "n_valid": int(nv.item()),
+        "loss": float(loss.item()), "n_valid": int(nv.item()), "bwd_schedule": sched,
         "roofline": roofline, "kernels": kernels, "input_generation_s": gen_s,
     }
     out["empirical_mfma_peak"] = mfma_probe(mst, torch)

@@ -163,6 +163,27 @@ mst_status mst_lmhead_ce_bwd(const void* H, const void* W, const int32_t* labels
                              void* stream);
 
 /*
+ * Order of the backward pass (Algorithm 4).  Both orders recompute every logit once, keep at most the
+ * bytes mst_workspace_bytes reports (one mini-sequence of fp32 logits, (S/M) * V * 4) and give the same
+ * dH and dW up to fp32 summation order; each is deterministic.
+ *   MST_BWD_SCHEDULE_PAIRS   the loop over mini-sequences as printed, two per dW pass: the block of dlogits
+ *                            alive at a time is 2 * ceil(S/M) rows by all of V; dW is read and rewritten
+ *                            once per pair.
+ *   MST_BWD_SCHEDULE_BLOCKS  the same bytes hold R rows by one window of the vocabulary (plus fp32 dH sums
+ *                            of the R rows), R as large as fits: dW of a window accumulates over the row
+ *                            blocks (no re-read at all when R covers S), dH of a row block over the windows.
+ *   MST_BWD_SCHEDULE_AUTO    (default) whichever a host-side cost model (rounds of workgroups plus fp32
+ *                            gradient traffic) ranks faster for the shape.
+ * mst_set_bwd_schedule: host, process-wide, takes effect at the next call; MST_ERR_BAD_SHAPE for an unknown
+ * value.  mst_bwd_schedule_info: host, pure; fills info[0..7] = {schedule that would run, rows per block,
+ * row blocks, vocabulary entries per window, windows, dH split count, cost estimate of PAIRS in us, of
+ * BLOCKS in us (0 if no block shape fits)}.
+ */
+enum { MST_BWD_SCHEDULE_AUTO = 0, MST_BWD_SCHEDULE_PAIRS = 1, MST_BWD_SCHEDULE_BLOCKS = 2 };
+mst_status mst_set_bwd_schedule(int32_t schedule);
+mst_status mst_bwd_schedule_info(int64_t S, int64_t d, int64_t V, int32_t M, int64_t* info);
+
+/*
  * Matrix-core probe (measurement aid, not part of the path).  Enqueues a kernel in
  * which every wave of `blocks` workgroups of 512 threads issues iters * 16
  * v_mfma_f32_32x32x16_bf16 instructions on register-resident operands (no LDS, no

@@ -65,6 +65,10 @@ def load_library() -> ctypes.CDLL:
     lib.mst_lmhead_ce_bwd.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int64, c.c_int64,
                                       c.c_int32, c.c_int32, c.c_float, c.c_void_p, c.c_void_p,
                                       c.c_void_p, c.c_size_t, c.c_void_p, c.c_void_p, c.c_void_p]
+    lib.mst_set_bwd_schedule.restype = c.c_int
+    lib.mst_set_bwd_schedule.argtypes = [c.c_int32]
+    lib.mst_bwd_schedule_info.restype = c.c_int
+    lib.mst_bwd_schedule_info.argtypes = [c.c_int64, c.c_int64, c.c_int64, c.c_int32, c.POINTER(c.c_int64)]
     lib.mst_profile_enable.restype = c.c_int
     lib.mst_profile_enable.argtypes = [c.c_int]
     lib.mst_profile_collect.restype = c.c_int
@@ -151,6 +155,21 @@ def mst_lmhead_ce_bwd(H, W, labels, ignore_index: int, M: int, grad_loss: float,
         _ptr(H), _ptr(W), _ptr(labels), S, d, V, ignore_index, M, float(grad_loss), _ptr(lse), _ptr(n_valid),
         _ptr(workspace), workspace.numel() * workspace.element_size(),
         _ptr(dH), _ptr(dW), _stream_handle(stream)))
+
+
+BWD_SCHEDULE_AUTO, BWD_SCHEDULE_PAIRS, BWD_SCHEDULE_BLOCKS = 0, 1, 2
+
+
+def mst_set_bwd_schedule(schedule: int) -> None:
+    _check(load_library().mst_set_bwd_schedule(int(schedule)))
+
+
+def mst_bwd_schedule_info(S: int, d: int, V: int, M: int) -> dict:
+    info = (ctypes.c_int64 * 8)()
+    _check(load_library().mst_bwd_schedule_info(S, d, V, M, info))
+    keys = ("schedule", "rows_per_block", "row_blocks", "vocab_per_window", "windows", "dh_split",
+            "est_pairs_us", "est_blocks_us")
+    return dict(zip(keys, (int(x) for x in info)))
 
 
 def mst_profile_enable(enable: bool) -> None:

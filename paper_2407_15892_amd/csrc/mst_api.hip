@@ -6,14 +6,18 @@
 #include "host_util.hpp"
 #include "mst_kernels.hpp"
 
+#include <atomic>
 #include <mutex>
 
 namespace {
 
 using namespace mst;
 
-constexpr int kNumCu = 256;          // MI355X compute units; only steers the dH split choice
+constexpr int kNumCu = 256;          // MI355X compute units; only steers the schedule choices (splits, blocks)
 constexpr int kMaxDhSplit = 16;
+constexpr int kMaxWindows = 64;      // most vocabulary windows the block schedule considers
+
+std::atomic<int> g_bwd_schedule{MST_BWD_SCHEDULE_AUTO};
 
 using mst_host::align_up;
 using mst_host::misaligned;
@@ -38,7 +42,97 @@ struct Plan {
   size_t b_lse;       // offset of the lse scratch used when lse is not supplied
   size_t b_fwd;       // offset of the forward region used when lse is not supplied
   size_t b_total_max; // bytes needed when neither lse nor n_valid is supplied
+  // Block schedule of the backward pass (used when blk_use): the same b_total bytes hold dlogits of blk_rows rows
+  // by blk_win_tiles * kTile vocabulary entries (bf16, leading dimension blk_ldg) and, behind it, fp32 dH sums of
+  // blk_rows x d.  blk_n_rb row blocks x blk_n_win vocabulary windows cover S x V.
+  bool blk_use;
+  int blk_rows, blk_n_rb, blk_win_tiles, blk_n_win, blk_ldg;
+  size_t blk_acc;     // byte offset of the dH sums
+  double est_pairs_us, est_blocks_us;   // the cost model's figures (for the record; see choose_schedule)
 };
+
+// ------------------------------------------------------------------ backward schedule
+// Both schedules recompute each logit once and keep at most b_total bytes of dlogits alive; they differ in
+// which block of the S x V dlogits matrix is alive at a time and therefore in how often the fp32 gradients
+// are read back and rewritten:
+//   pairs   (Algorithm 4 as printed, two mini-sequences per dW pass): blocks of 2C rows x all of V.
+//           dW is read and rewritten once per pair after the first; dH is final after each chunk.
+//   blocks  R rows x one window of the vocabulary, R as large as the same bytes allow (dlogits of the block
+//           plus fp32 dH sums of its rows).  dW of a window accumulates over the row blocks (none to add when
+//           R covers S), dH of a row block accumulates over the windows (S*d*4 bytes, far smaller than dW when
+//           V >> d).
+// The estimate counts rounds of kNumCu workgroups per launch at a nominal time per K step, plus the fp32
+// gradient traffic at a nominal bandwidth; it only has to rank the candidates.
+constexpr double kUsPerKStep = 1.5;      // one 256 x 256 x 64 block-tile step with one workgroup per CU
+constexpr double kRmwBytesPerUs = 4.0e6; // fp32 read-modify-write streams next to a running GEMM
+double rounds_us(int64_t tiles, int64_t k) {
+  return (double)((tiles + kNumCu - 1) / kNumCu) * (double)((k + kBK - 1) / kBK) * kUsPerKStep;
+}
+
+void choose_schedule(Plan* p) {
+  const int64_t S = p->S, d = p->d, V = p->V, C = p->C;
+  const int n_vt = p->n_vt, n_jt = p->n_jt;
+  // pairs
+  double pairs = 0.0;
+  for (int ia = 0; ia < p->n_chunks; ia += 2) {
+    int64_t rows_pair = 0;
+    for (int i = ia; i < ia + 2 && i < p->n_chunks; ++i) {
+      const int64_t rows = (S - (int64_t)i * C) < C ? (S - (int64_t)i * C) : C;
+      const int64_t n_st = (rows + kTile - 1) / kTile;
+      rows_pair += rows;
+      pairs += rounds_us(n_st * n_vt, d);                                                  // dlogits
+      pairs += rounds_us(n_st * n_jt * p->dh_split, (int64_t)p->dh_ksteps * kBK);           // dH
+      if (p->dh_split > 1) pairs += 2.0 * (double)(p->dh_split * rows * d * 4) / kRmwBytesPerUs;
+    }
+    pairs += rounds_us((int64_t)n_vt * n_jt, rows_pair);                                   // dW
+    pairs += (double)((ia > 0 ? 8 : 4) * V * d) / kRmwBytesPerUs;
+  }
+  p->est_pairs_us = pairs;
+  // blocks: for every window count, the largest row block that fits, then rows balanced over the blocks
+  p->blk_use = false;
+  p->est_blocks_us = 0.0;
+  double best = 0.0;
+  for (int n_win = 2; n_win <= kMaxWindows && n_win <= n_vt; ++n_win) {
+    const int win_tiles = (n_vt + n_win - 1) / n_win;
+    const int n_win_eff = (n_vt + win_tiles - 1) / win_tiles;
+    if (n_win_eff != n_win) continue;                       // same partition as a smaller count
+    const int64_t ldg_w = (int64_t)win_tiles * kTile;
+    const int64_t per_row = ldg_w * 2 + d * 4;
+    if (p->b_total < 256 + (size_t)per_row * kTile) continue;
+    int64_t R = (int64_t)((p->b_total - 256) / (size_t)per_row) / kTile * kTile;
+    const int64_t S_up = (S + kTile - 1) / kTile * kTile;
+    if (R > S_up) R = S_up;
+    const int n_rb = (int)((S + R - 1) / R);
+    R = ((S + n_rb - 1) / n_rb + kTile - 1) / kTile * kTile;
+    if (R * ldg_w >= (int64_t(1) << 30) || R * d >= (int64_t(1) << 30)) continue;   // 32-bit offsets inside a block
+    double t = 0.0;
+    for (int rb = 0; rb < n_rb; ++rb) {
+      const int64_t rows = (S - rb * R) < R ? (S - rb * R) : R;
+      const int64_t n_st = (rows + kTile - 1) / kTile;
+      for (int w = 0; w < n_win; ++w) {
+        const int64_t tiles_w = (w + 1) * win_tiles <= n_vt ? win_tiles : n_vt - w * win_tiles;
+        const int64_t cols = tiles_w * kTile < V - (int64_t)w * ldg_w ? tiles_w * kTile : V - (int64_t)w * ldg_w;
+        t += rounds_us(n_st * tiles_w, d);                                                 // dlogits
+        t += rounds_us(n_st * n_jt, cols);                                                 // dH
+        t += (double)((w > 0 ? 4 : 0) + (w + 1 < n_win ? 4 : 2)) * (double)(rows * d) / kRmwBytesPerUs;
+        t += rounds_us(tiles_w * n_jt, rows);                                              // dW
+        t += (double)((rb > 0 ? 8 : 4) * cols * d) / kRmwBytesPerUs;
+      }
+    }
+    if (!p->blk_use || t < best) {
+      best = t;
+      p->blk_use = true;
+      p->blk_rows = (int)R; p->blk_n_rb = n_rb; p->blk_win_tiles = win_tiles; p->blk_n_win = n_win;
+      p->blk_ldg = (int)ldg_w;
+      p->blk_acc = align_up((size_t)R * ldg_w * 2, 256);
+    }
+  }
+  p->est_blocks_us = best;
+  const int forced = g_bwd_schedule.load();
+  if (forced == MST_BWD_SCHEDULE_PAIRS) p->blk_use = false;
+  else if (forced == MST_BWD_SCHEDULE_AUTO && p->blk_use && !(best < pairs)) p->blk_use = false;
+  // MST_BWD_SCHEDULE_BLOCKS keeps the best block shape whenever one fits
+}
 
 mst_status make_plan(int64_t S, int64_t d, int64_t V, int32_t M, Plan* p) {
   if (S <= 0 || d <= 0 || V <= 0) return MST_ERR_BAD_SHAPE;
@@ -85,6 +179,7 @@ mst_status make_plan(int64_t S, int64_t d, int64_t V, int32_t M, Plan* p) {
   p->b_lse = p->b_ctl + sizeof(Control);
   p->b_fwd = p->b_lse + align_up((size_t)S * 4, 256);
   p->b_total_max = p->b_fwd + p->f_total;
+  choose_schedule(p);
   return MST_OK;
 }
 
@@ -275,9 +370,9 @@ mst_status mst_lmhead_ce_bwd(const void* H, const void* W, const int32_t* labels
     const int64_t r0 = (int64_t)i * p.C;
     const int rows = rows_of(i), n_st = (rows + kTile - 1) / kTile;
     Scope sc(st, MST_K_BWD_GEMM_DLOGITS);
-    hipLaunchKernelGGL(k_bwd_gemm_dlogits, dim3(xcd_grid(n_st * p.n_vt)), dim3(kThreads), kLdsBytes, st,
-                       Hb + r0 * p.d, Wb, labels + r0, lse + r0, rows, (int)p.d, (int)p.V, ignore_index, n_st, p.n_vt,
-                       G, p.ldg);
+    hipLaunchKernelGGL(k_bwd_gemm_dlogits, dim3(xcd_grid_2d(p.n_vt, n_st)), dim3(kThreads), kLdsBytes, st,
+                       Hb + r0 * p.d, Wb, labels + r0, lse + r0, rows, (int)p.d, (int)p.V, 0, (int)p.V, ignore_index,
+                       n_st, p.n_vt, G, p.ldg);
   };
   auto grad_h = [&](int i, const __bf16* G, void* partial_space) {
     const int64_t r0 = (int64_t)i * p.C;
@@ -286,7 +381,7 @@ mst_status mst_lmhead_ce_bwd(const void* H, const void* W, const int32_t* labels
     {
       Scope sc(st, MST_K_BWD_GEMM_DH);
       hipLaunchKernelGGL(k_bwd_gemm_dh, dim3(xcd_grid(n_st * p.n_jt * p.dh_split)), dim3(kThreads), kLdsBytes, st,
-                         G, p.ldg, Wb, rows, (int)p.d, (int)p.V, n_st, p.n_jt, p.dh_split, p.dh_ksteps,
+                         G, p.ldg, Wb, rows, (int)p.d, (int)p.V, n_st, p.n_jt, p.dh_split, p.dh_ksteps, kDhSplit,
                          nv, grad_loss, partial, p.C, dHb + r0 * p.d);
     }
     if (p.dh_split > 1) {
@@ -304,6 +399,46 @@ mst_status mst_lmhead_ce_bwd(const void* H, const void* W, const int32_t* labels
                        i_first > 0 ? 1 : 0, i_last == p.n_chunks - 1 ? 1 : 0, nv, grad_loss, dW);
   };
 
+  if (p.blk_use) {
+    // Block schedule: for each block of rows, walk the vocabulary windows.  Per (row block, window):
+    //   dlogits of the block -> workspace | dH sums of the row block (+)= G W_window | dW_window (+)= G^T H_block
+    // dH of a row block is final after its last window, dW of a window after the last row block; both
+    // accumulate in a fixed order.
+    __bf16* G = reinterpret_cast<__bf16*>(ws);
+    float* dh_sums = reinterpret_cast<float*>(ws + p.blk_acc);
+    for (int rb = 0; rb < p.blk_n_rb; ++rb) {
+      const int64_t r0 = (int64_t)rb * p.blk_rows;
+      const int rows = (int)((p.S - r0) < p.blk_rows ? (p.S - r0) : p.blk_rows);
+      const int n_st = (rows + kTile - 1) / kTile;
+      for (int w = 0; w < p.blk_n_win; ++w) {
+        const int t0 = w * p.blk_win_tiles;
+        const int tiles_w = t0 + p.blk_win_tiles <= p.n_vt ? p.blk_win_tiles : p.n_vt - t0;
+        const int64_t v_base = (int64_t)t0 * kTile;
+        const int Vw = (int)((p.V - v_base) < (int64_t)tiles_w * kTile ? (p.V - v_base) : (int64_t)tiles_w * kTile);
+        {
+          Scope sc(st, MST_K_BWD_GEMM_DLOGITS);
+          hipLaunchKernelGGL(k_bwd_gemm_dlogits, dim3(xcd_grid_2d(tiles_w, n_st)), dim3(kThreads), kLdsBytes, st,
+                             Hb + r0 * p.d, Wb + v_base * p.d, labels + r0, lse + r0, rows, (int)p.d, Vw, (int)v_base,
+                             (int)p.V, ignore_index, n_st, tiles_w, G, p.blk_ldg);
+        }
+        {
+          Scope sc(st, MST_K_BWD_GEMM_DH);
+          const int mode = w == 0 ? kDhFirst : (w == p.blk_n_win - 1 ? kDhLast : kDhAdd);
+          hipLaunchKernelGGL(k_bwd_gemm_dh, dim3(xcd_grid_2d(n_st, p.n_jt)), dim3(kThreads), kLdsBytes, st,
+                             G, p.blk_ldg, Wb + v_base * p.d, rows, (int)p.d, Vw, n_st, p.n_jt, 1, (Vw + kBK - 1) / kBK, mode,
+                             nv, grad_loss, dh_sums, p.blk_rows, dHb + r0 * p.d);
+        }
+        {
+          Scope sc(st, MST_K_BWD_GEMM_DW);
+          hipLaunchKernelGGL(k_bwd_gemm_dw, dim3(xcd_grid_2d(tiles_w, p.n_jt)), dim3(kThreads), kLdsBytes, st,
+                             G, p.blk_ldg, Hb + r0 * p.d, rows, (int)p.d, Vw, tiles_w, p.n_jt,
+                             rb > 0 ? 1 : 0, rb == p.blk_n_rb - 1 ? 1 : 0, nv, grad_loss, dW + v_base * p.d);
+        }
+      }
+    }
+    return check_launch();
+  }
+
   // Algorithm 4's loop over mini-sequences, two at a time: the chunk pair (A, B) shares one dW pass.
   //   dlogits(A) -> slot 0 | dH(A), partials in slot 1 | dlogits(B) -> slot 1 | dW += [G_A; G_B]^T [H_A; H_B]
   //   | dH(B), partials in slot 0
@@ -320,6 +455,29 @@ mst_status mst_lmhead_ce_bwd(const void* H, const void* W, const int32_t* labels
     }
   }
   return check_launch();
+}
+
+mst_status mst_set_bwd_schedule(int32_t schedule) {
+  if (schedule != MST_BWD_SCHEDULE_AUTO && schedule != MST_BWD_SCHEDULE_PAIRS && schedule != MST_BWD_SCHEDULE_BLOCKS)
+    return MST_ERR_BAD_SHAPE;
+  g_bwd_schedule.store(schedule);
+  return MST_OK;
+}
+
+mst_status mst_bwd_schedule_info(int64_t S, int64_t d, int64_t V, int32_t M, int64_t* info) {
+  if (!info) return MST_ERR_NULL_POINTER;
+  Plan p;
+  const mst_status s = make_plan(S, d, V, M, &p);
+  if (s != MST_OK) return s;
+  info[0] = p.blk_use ? MST_BWD_SCHEDULE_BLOCKS : MST_BWD_SCHEDULE_PAIRS;
+  info[1] = p.blk_use ? p.blk_rows : 2 * (int64_t)p.C;
+  info[2] = p.blk_use ? p.blk_n_rb : (p.n_chunks + 1) / 2;
+  info[3] = p.blk_use ? (int64_t)p.blk_win_tiles * kTile : p.V;
+  info[4] = p.blk_use ? p.blk_n_win : 1;
+  info[5] = p.blk_use ? 1 : p.dh_split;
+  info[6] = (int64_t)p.est_pairs_us;
+  info[7] = (int64_t)p.est_blocks_us;
+  return MST_OK;
 }
 
 mst_status mst_profile_enable(int enable) {

@@ -336,14 +336,17 @@ __global__ __launch_bounds__(1024) void k_loss_reduce(const float* __restrict__ 
 //   (kept unscaled so that the label entry p - 1 stays within 2^-9 of -1, its nearest bf16 neighbour in most
 //   rows; the factor gamma = grad_loss / N_valid is applied in fp32 by the two gradient GEMMs)
 // ---------------------------------------------------------------------------
+// The kernel works on a window of the vocabulary: W points at the window's first row, V is the number of
+// vocabulary entries from there on, G column 0 is the window's first entry; v_base is that entry's absolute
+// index and V_all the whole vocabulary (both only for the labels).  The row-chunk schedule passes the whole
+// vocabulary (v_base = 0, V = V_all).
 __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dlogits(
     const __bf16* __restrict__ Hc, const __bf16* __restrict__ W, const int* __restrict__ labels_c,
-    const float* __restrict__ lse_c, int rows, int d, int V, int ignore_index, int n_st, int n_vt,
+    const float* __restrict__ lse_c, int rows, int d, int V, int v_base, int V_all, int ignore_index, int n_st, int n_vt,
     __bf16* __restrict__ G, int ldg) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  const int w = xcd_work_item(n_st * n_vt);
-  if (w < 0) return;
-  const int vt = w / n_st, st = w - vt * n_st;
+  int vt, st;                                        // an XCD's resident workgroups: 8 vocabulary x 4 row tiles
+  if (!xcd_tile_2d(n_vt, n_st, &vt, &st)) return;
   const int v0 = vt * kTile, s0 = st * kTile;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -362,8 +365,9 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dlogits(
   for (int u = 0; u < kTB16; ++u) {
     const int s_local = s0 + wb * 64 + 16 * u + (lane & 15);
     if (s_local >= rows) continue;
-    const int y = labels_c[s_local];
-    const bool valid = (y != ignore_index) && ((unsigned)y < (unsigned)V);
+    const int y_abs = labels_c[s_local];
+    const bool valid = (y_abs != ignore_index) && ((unsigned)y_abs < (unsigned)V_all);
+    const int y = y_abs - v_base;                    // position in the window; outside [0, V) if the label is elsewhere
     const float lb = lse_c[s_local] * kLog2e;
     __bf16* grow = G + (size_t)s_local * ldg;
 #pragma unroll
@@ -386,18 +390,31 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dlogits(
 // backward 2: dH_chunk = G W over a range of the vocabulary
 //   A side = chunk rows (G, K-contiguous), B side = hidden index j (W, K-strided)
 // ---------------------------------------------------------------------------
+// mode (the kDh* constants):
+//   kDhSplit  one launch covers the whole contraction: n_split > 1 writes fp32 partials for k_bwd_dh_reduce,
+//             n_split == 1 writes gamma * result as bf16 (the row-chunk schedule)
+//   kDhFirst / kDhAdd / kDhLast  the contraction arrives in several launches, one per vocabulary window
+//             (n_split must be 1): the first stores the fp32 sums into partial[rows_stride][d], the middle ones add
+//             to them, the last adds and writes gamma * total as bf16.  Launches run in order on one stream, so
+//             the summation order is fixed.
+constexpr int kDhSplit = 0, kDhFirst = 1, kDhAdd = 2, kDhLast = 3;
 __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dh(
     const __bf16* __restrict__ G, int ldg, const __bf16* __restrict__ W, int rows, int d, int V,
-    int n_st, int n_jt, int n_split, int ksteps_per_split,
+    int n_st, int n_jt, int n_split, int ksteps_per_split, int mode,
     const long long* __restrict__ n_valid, float grad_loss,
-    float* __restrict__ partial /* [n_split][rows_stride][d], used when n_split > 1 */, int rows_stride,
-    __bf16* __restrict__ dHc /* used when n_split == 1 */) {
+    float* __restrict__ partial /* [n_split][rows_stride][d] */, int rows_stride,
+    __bf16* __restrict__ dHc /* written by kDhSplit with n_split == 1 and by kDhLast */) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  const int w = xcd_work_item(n_st * n_jt * n_split);
-  if (w < 0) return;
-  const int st = w % n_st;
-  const int jt = (w / n_st) % n_jt;
-  const int sp = w / (n_st * n_jt);
+  int st, jt, sp = 0;
+  if (mode == kDhSplit) {
+    const int w = xcd_work_item(n_st * n_jt * n_split);
+    if (w < 0) return;
+    st = w % n_st;
+    jt = (w / n_st) % n_jt;
+    sp = w / (n_st * n_jt);
+  } else if (!xcd_tile_2d(n_st, n_jt, &st, &jt)) {   // many row tiles: rectangles of row x hidden tiles per XCD
+    return;
+  }
   const int s0 = st * kTile, j0 = jt * kTile;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -414,6 +431,25 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dh(
   pb.init(W + j0, d, V, d - j0, wave, lane, wb);
   gemm_mainloop_pp<Tile16>(acc, pa, pb, smem, k_begin, k_end, wa);
 
+  if (mode == kDhAdd || mode == kDhLast) {
+    // running sums of the earlier windows: all loads first (the fragment registers are free now), then the adds
+#pragma unroll
+    for (int t = 0; t < kTA16; ++t)
+#pragma unroll
+      for (int u = 0; u < kTB16; ++u) {
+        const int j = j0 + wb * 64 + 16 * u + (lane & 15);
+        f32x4 old = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int s_local = s0 + wa * 128 + a_index_in_block16<false>(t, r, lane);
+          if (s_local < rows && j < d) old[r] = __builtin_nontemporal_load(partial + (size_t)s_local * d + j);
+        }
+        acc[t][u] += old;
+      }
+  }
+  const bool to_bf16 = mode == kDhLast || (mode == kDhSplit && n_split == 1);
+  const float gamma = to_bf16 ? gamma_of(n_valid, grad_loss) : 1.0f;
+  float* part = mode == kDhSplit ? partial + (size_t)sp * rows_stride * d : partial;
 #pragma unroll
   for (int t = 0; t < kTA16; ++t)
 #pragma unroll
@@ -423,8 +459,8 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dh(
       for (int r = 0; r < 4; ++r) {
         const int s_local = s0 + wa * 128 + a_index_in_block16<false>(t, r, lane);
         if (s_local < rows && j < d) {
-          if (n_split > 1) partial[((size_t)sp * rows_stride + s_local) * d + j] = acc[t][u][r];
-          else dHc[(size_t)s_local * d + j] = (__bf16)(gamma_of(n_valid, grad_loss) * acc[t][u][r]);
+          if (to_bf16) dHc[(size_t)s_local * d + j] = (__bf16)(gamma * acc[t][u][r]);
+          else part[(size_t)s_local * d + j] = acc[t][u][r];
         }
       }
     }

@@ -77,3 +77,24 @@ def test_fullsize_config_matches_oracle_on_samples(cfg_index):
     run.forward()
     _, dW2 = run.backward()
     assert torch.equal(dW_first.view(torch.int32), dW2.view(torch.int32))
+
+    # --- the other order of the backward pass against the same references
+    import paper_2407_15892_amd as mst
+    chosen = mst.mst_bwd_schedule_info(cfg.S, cfg.d, cfg.V, cfg.M)
+    other = mst.BWD_SCHEDULE_PAIRS if chosen["schedule"] == mst.BWD_SCHEDULE_BLOCKS else mst.BWD_SCHEDULE_BLOCKS
+    try:
+        mst.mst_set_bwd_schedule(other)
+        forced = mst.mst_bwd_schedule_info(cfg.S, cfg.d, cfg.V, cfg.M)
+        print(f"cfg {cfg_index}: default schedule {chosen}, also run {forced}", flush=True)
+        if forced["schedule"] == other:
+            dH_o, dW_o = run.backward()
+            dH_os = bf16_tensor_to_f64(dH_o[torch.from_numpy(rows).cuda()])
+            dW_os = dW_o[torch.from_numpy(vrows).cuda()].cpu().numpy().astype(np.float64)
+            assert np.abs(dH_os - dH_ref).max() <= GRAD_TOL * np.abs(dH_ref).max()
+            assert np.abs(dW_os - dW_ref).max() <= GRAD_TOL * np.abs(dW_ref).max()
+            assert float(dH_o[ign].float().abs().max()) == 0.0
+            assert torch.isfinite(dW_o).all() and torch.isfinite(dH_o.float()).all()
+            # both orders form the same products; only the fp32 summation order differs
+            assert float((dW_o - dW_first).abs().max()) <= 1e-3 * float(dW_first.abs().max())
+    finally:
+        mst.mst_set_bwd_schedule(mst.BWD_SCHEDULE_AUTO)

@@ -261,3 +261,70 @@ def test_shifted_labels_feed_the_forward_pass():
     loss, _, nv = run.forward()
     assert nv == int((shifted != -100).sum())
     assert abs(loss - ref_loss) <= LOSS_RTOL * abs(ref_loss)
+
+
+# ---- the two orders of the backward pass
+
+@pytest.fixture
+def schedule():
+    """Forces a backward schedule for one test and restores the default afterwards."""
+    import paper_2407_15892_amd as mst
+
+    def force(which):
+        mst.mst_set_bwd_schedule(which)
+    yield force
+    mst.mst_set_bwd_schedule(mst.BWD_SCHEDULE_AUTO)
+
+
+@pytest.mark.parametrize("S,d,V,M,blocks,windows", [
+    (1024, 128, 3000, 8, 2, 3),     # two row blocks of 512 rows, three windows, ragged last window (V = 11.7 tiles)
+    (1000, 136, 2900, 4, 1, 3),     # one ragged row block, d not a multiple of 64
+    (1400, 72, 5000, 12, 2, 4),     # ragged second row block (768 + 632 rows)
+    (1800, 136, 2900, 12, 3, 4),    # three row blocks: dW stored, accumulated, accumulated and scaled
+    (600, 64, 70000, 1, 1, 2),      # wide windows, V not a multiple of 8
+])
+def test_block_schedule_matches_oracle(schedule, S, d, V, M, blocks, windows):
+    """Row blocks x vocabulary windows: dW accumulates over row blocks, dH over windows."""
+    import paper_2407_15892_amd as mst
+    schedule(mst.BWD_SCHEDULE_BLOCKS)
+    info = mst.mst_bwd_schedule_info(S, d, V, M)
+    assert info["schedule"] == mst.BWD_SCHEDULE_BLOCKS and info["row_blocks"] == blocks and info["windows"] == windows, info
+    cfg = mi.custom_config(S, d, V, M, index=400 + S % 97, w_std=0.3, ignore_frac=0.1, label_dist="zipf")
+    _check_full(mi.make_inputs(cfg), grad_loss=0.8)
+    _check_full(mi.make_inputs(cfg), grad_loss=0.8, use_lse=False)
+
+
+def test_block_and_pair_schedules_agree_and_repeat_bit_for_bit(schedule):
+    DeviceRun, bf2f = _harness()
+    import torch
+    import paper_2407_15892_amd as mst
+    inp = mi.make_inputs(mi.custom_config(1024, 256, 6000, 4, index=411, w_std=0.3, ignore_frac=0.05))
+    out = {}
+    for which in (mst.BWD_SCHEDULE_PAIRS, mst.BWD_SCHEDULE_BLOCKS):
+        schedule(which)
+        assert mst.mst_bwd_schedule_info(1024, 256, 6000, 4)["schedule"] == which
+        run = DeviceRun(inp)
+        run.forward()
+        dH0, dW0 = run.backward()
+        dH0, dW0 = dH0.clone(), dW0.clone()
+        for _ in range(2):
+            dH1, dW1 = run.backward()
+            assert torch.equal(dW0.view(torch.int32), dW1.view(torch.int32))
+            assert torch.equal(dH0.view(torch.int16), dH1.view(torch.int16))
+        out[which] = (bf2f(dH0), dW0.cpu().numpy().astype(np.float64))
+    (hA, wA), (hB, wB) = out[mst.BWD_SCHEDULE_PAIRS], out[mst.BWD_SCHEDULE_BLOCKS]
+    # same products, different fp32 summation order (and one more bf16 rounding point for neither)
+    assert np.abs(hA - hB).max() <= 2.0 ** -7 * np.abs(hA).max()
+    assert np.abs(wA - wB).max() <= 1e-4 * np.abs(wA).max()
+
+
+def test_block_schedule_does_not_overrun_the_workspace(schedule):
+    import paper_2407_15892_amd as mst
+    DeviceRun, _ = _harness()
+    schedule(mst.BWD_SCHEDULE_BLOCKS)
+    inp = mi.make_inputs(mi.custom_config(1024, 128, 3000, 8, index=412))
+    run = DeviceRun(inp, pad_workspace=4096)
+    run.forward()
+    run.backward()
+    tail = run.last_ws[-4096:]
+    assert bool((tail == 0xA5).all())

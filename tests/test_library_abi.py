@@ -125,3 +125,36 @@ def test_mfma_probe_argument_errors(mst):
     assert lib.mst_mfma_probe(8, 0, 1.0, fake, None) == -2
     assert lib.mst_mfma_probe(8, (1 << 20) + 1, 1.0, fake, None) == -2
     assert lib.mst_mfma_probe(8, 10, 1.0, None, None) == -1
+
+
+def test_backward_schedule_choice_and_block_shapes(mst):
+    """Host-only: which order of the backward pass the cost model picks, and that a block shape always fits the
+    bytes mst_workspace_bytes reports."""
+    try:
+        for cfg in mi.CONFIGS.values():
+            _, cap = mst.mst_workspace_bytes(cfg.S, cfg.d, cfg.V, cfg.M)
+            mst.mst_set_bwd_schedule(mst.BWD_SCHEDULE_AUTO)
+            auto = mst.mst_bwd_schedule_info(cfg.S, cfg.d, cfg.V, cfg.M)
+            mst.mst_set_bwd_schedule(mst.BWD_SCHEDULE_PAIRS)
+            pairs = mst.mst_bwd_schedule_info(cfg.S, cfg.d, cfg.V, cfg.M)
+            assert pairs["schedule"] == mst.BWD_SCHEDULE_PAIRS
+            assert pairs["rows_per_block"] == 2 * cfg.C and pairs["windows"] == 1 and pairs["vocab_per_window"] == cfg.V
+            mst.mst_set_bwd_schedule(mst.BWD_SCHEDULE_BLOCKS)
+            blocks = mst.mst_bwd_schedule_info(cfg.S, cfg.d, cfg.V, cfg.M)
+            if blocks["schedule"] == mst.BWD_SCHEDULE_BLOCKS:
+                R, Vw = blocks["rows_per_block"], blocks["vocab_per_window"]
+                assert R % 256 == 0 and Vw % 256 == 0 and blocks["windows"] >= 2
+                assert blocks["row_blocks"] == -(-cfg.S // R) and blocks["windows"] == -(-cfg.V // Vw)
+                # dlogits of the block (bf16) and the fp32 dH sums of its rows fit the same bytes
+                assert R * Vw * 2 + R * cfg.d * 4 + 256 <= cap, (cfg.name, blocks, cap)
+            # the automatic choice is the cheaper estimate
+            want = mst.BWD_SCHEDULE_BLOCKS if 0 < auto["est_blocks_us"] < auto["est_pairs_us"] else mst.BWD_SCHEDULE_PAIRS
+            assert auto["schedule"] == want, (cfg.name, auto)
+        # large vocabulary, short chunks: blocks; tiny problems: pairs
+        mst.mst_set_bwd_schedule(mst.BWD_SCHEDULE_AUTO)
+        assert mst.mst_bwd_schedule_info(8192, 4096, 128256, 8)["schedule"] == mst.BWD_SCHEDULE_BLOCKS
+        assert mst.mst_bwd_schedule_info(512, 256, 4096, 4)["schedule"] == mst.BWD_SCHEDULE_PAIRS
+        with pytest.raises(mst.MstError):
+            mst.mst_set_bwd_schedule(7)
+    finally:
+        mst.mst_set_bwd_schedule(mst.BWD_SCHEDULE_AUTO)
