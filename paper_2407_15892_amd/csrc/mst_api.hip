@@ -199,7 +199,8 @@ void set_kernel_attributes() {
   set((const void*)k_fwd_gemm_lse);
   set((const void*)k_bwd_gemm_dlogits);
   set((const void*)k_bwd_gemm_dh);
-  set((const void*)k_bwd_gemm_dw);
+  set((const void*)k_bwd_gemm_dw<false>);
+  set((const void*)k_bwd_gemm_dw<true>);
 }
 
 mst_status check_launch() { return hipGetLastError() == hipSuccess ? MST_OK : MST_ERR_LAUNCH; }
@@ -394,9 +395,10 @@ mst_status mst_lmhead_ce_bwd(const void* H, const void* W, const int32_t* labels
   auto grad_w = [&](int i_first, int i_last, int rows) {
     const int64_t r0 = (int64_t)i_first * p.C;
     Scope sc(st, MST_K_BWD_GEMM_DW);
-    hipLaunchKernelGGL(k_bwd_gemm_dw, dim3(xcd_grid_2d(p.n_vt, p.n_jt)), dim3(kThreads), kLdsBytes, st,
+    hipLaunchKernelGGL(i_first > 0 ? k_bwd_gemm_dw<false> : k_bwd_gemm_dw<true>, dim3(xcd_grid_2d(p.n_vt, p.n_jt)),
+                       dim3(kThreads), kLdsBytes, st,
                        slot[0], p.ldg, Hb + r0 * p.d, rows, (int)p.d, (int)p.V, p.n_vt, p.n_jt,
-                       i_first > 0 ? 1 : 0, i_last == p.n_chunks - 1 ? 1 : 0, nv, grad_loss, dW);
+                       i_last == p.n_chunks - 1 ? 1 : 0, nv, grad_loss, dW);
   };
 
   if (p.blk_use) {
@@ -430,9 +432,10 @@ mst_status mst_lmhead_ce_bwd(const void* H, const void* W, const int32_t* labels
         }
         {
           Scope sc(st, MST_K_BWD_GEMM_DW);
-          hipLaunchKernelGGL(k_bwd_gemm_dw, dim3(xcd_grid_2d(tiles_w, p.n_jt)), dim3(kThreads), kLdsBytes, st,
+          hipLaunchKernelGGL(rb > 0 ? k_bwd_gemm_dw<false> : k_bwd_gemm_dw<true>, dim3(xcd_grid_2d(tiles_w, p.n_jt)),
+                             dim3(kThreads), kLdsBytes, st,
                              G, p.blk_ldg, Hb + r0 * p.d, rows, (int)p.d, Vw, tiles_w, p.n_jt,
-                             rb > 0 ? 1 : 0, rb == p.blk_n_rb - 1 ? 1 : 0, nv, grad_loss, dW + v_base * p.d);
+                             rb == p.blk_n_rb - 1 ? 1 : 0, nv, grad_loss, dW + v_base * p.d);
         }
       }
     }

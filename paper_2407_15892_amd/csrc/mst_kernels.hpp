@@ -570,15 +570,76 @@ __device__ __forceinline__ void dw_tile(
     }
 }
 
+// The same tile on the 16x16x32 instruction.  Its main loop is a few percent faster, its fp32 pass slower (a
+// store covers 4 rows x 64 bytes instead of 2 rows x 128): it serves the passes that only store (the first
+// row block of a dW pass, or the only one), dw_tile the passes that also read dW back.
+__device__ __forceinline__ void dw_tile16(
+    const __bf16* __restrict__ G, int ldg, int g_cols, const __bf16* __restrict__ Hc, int ldh, int rows, int d, int V,
+    int vt, int jt, int accumulate, float scale, float* __restrict__ dW, int ldw, char* smem) {
+  const int v0 = vt * kTile, j0 = jt * kTile;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wa = wave >> 2, wb = wave & 3;
+  const int rows_valid = V - v0 < kTile ? V - v0 : kTile;
+  const __amdgpu_buffer_rsrc_t out = make_rsrc_uniform(dW + (size_t)v0 * ldw, (uint32_t)rows_valid * (uint32_t)ldw * 4u);
+  constexpr int kNonTemporal = 2;
+  uint32_t lane_off[kTB16];
+  bool col_ok[kTB16];
+#pragma unroll
+  for (int u = 0; u < kTB16; ++u) {
+    const int j = j0 + wb * 64 + 16 * u + (lane & 15);
+    col_ok[u] = j < d;
+    lane_off[u] = ((uint32_t)(wa * 128 + 4 * (lane >> 4)) * (uint32_t)ldw + (uint32_t)j) * 4u;
+  }
+  auto row_off = [&](int t, int r) { return (uint32_t)(16 * t + r) * (uint32_t)ldw * 4u; };
+  f32x4 acc[kTA16][kTB16];
+  zero_acc<kTA16, kTB16>(acc);
+  if (accumulate) {
+#pragma unroll
+    for (int u = 0; u < kTB16; ++u)
+      if (col_ok[u]) {
+#pragma unroll
+        for (int t = 0; t < kTA16; ++t)
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            acc[t][u][r] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(out, lane_off[u] + row_off(t, r), 0, kNonTemporal));
+      }
+#pragma unroll
+    for (int t = 0; t < kTA16; ++t)
+#pragma unroll
+      for (int u = 0; u < kTB16; ++u) asm volatile("" : "+v"(acc[t][u]));
+  }
+  PanelKS16<Tile16, kTile, kTA16> pa;
+  PanelKS16<Tile16, kTile, kTB16> pb;
+  pa.init(G + v0, ldg, rows, g_cols - v0, wave, lane, wa);
+  pb.init(Hc + j0, ldh, rows, d - j0, wave, lane, wb);
+  gemm_mainloop_pp<Tile16>(acc, pa, pb, smem, 0, rows, wa);
+#pragma unroll
+  for (int t = 0; t < kTA16; ++t)
+#pragma unroll
+    for (int u = 0; u < kTB16; ++u) acc[t][u] *= scale;
+#pragma unroll
+  for (int u = 0; u < kTB16; ++u)
+    if (col_ok[u]) {
+#pragma unroll
+      for (int t = 0; t < kTA16; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[t][u][r]), out, lane_off[u] + row_off(t, r), 0, kNonTemporal);
+    }
+}
+
+template <bool kStoreOnly>
 __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dw(
     const __bf16* __restrict__ G, int ldg, const __bf16* __restrict__ Hc, int rows, int d, int V,
-    int n_vt, int n_jt, int accumulate, int last, const long long* __restrict__ n_valid, float grad_loss,
+    int n_vt, int n_jt, int last, const long long* __restrict__ n_valid, float grad_loss,
     float* __restrict__ dW) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   int vt, jt;
   if (!xcd_tile_2d(n_vt, n_jt, &vt, &jt)) return;
   const float scale = last ? gamma_of(n_valid, grad_loss) : 1.0f;
-  dw_tile(G, ldg, ldg, Hc, d, rows, d, V, vt, jt, accumulate, scale, dW, d, smem);
+  if (kStoreOnly) dw_tile16(G, ldg, ldg, Hc, d, rows, d, V, vt, jt, 0, scale, dW, d, smem);
+  else dw_tile(G, ldg, ldg, Hc, d, rows, d, V, vt, jt, 1, scale, dW, d, smem);
 }
 
 }  // namespace mst

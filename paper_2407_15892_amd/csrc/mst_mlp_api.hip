@@ -57,7 +57,8 @@ void set_kernel_attributes() {
   set((const void*)k_mlp_gemm_nt);
   set((const void*)k_mlp_gemm_nn<Tile16>);
   set((const void*)k_mlp_gemm_nn<Tile16HalfB>);
-  set((const void*)k_mlp_dw3);
+  set((const void*)k_mlp_dw3<false>);
+  set((const void*)k_mlp_dw3<true>);
 }
 
 mst_status check_launch() { return hipGetLastError() == hipSuccess ? MST_OK : MST_ERR_LAUNCH; }
@@ -232,8 +233,8 @@ mst_status mst_mlp_bwd(const void* X, const void* Wg, const void* Wu, const void
       ps.p[0] = dw_problem(bufG, dI, Xc, dd, dd, dI, dWg);     // dWg [I][d] (+)= dG^T X
       ps.p[1] = dw_problem(bufU, dI, Xc, dd, dd, dI, dWu);     // dWu [I][d] (+)= dU^T X
       ps.p[2] = dw_problem(dOc, dd, bufA, dI, dI, dd, dWd);    // dWd [d][I] (+)= dO^T A
-      hipLaunchKernelGGL(k_mlp_dw3, dim3(ps.p[0].grid + ps.p[1].grid + ps.p[2].grid), dim3(kThreads), kLdsBytes, st,
-                         ps, rows, acc);
+      hipLaunchKernelGGL(acc ? k_mlp_dw3<false> : k_mlp_dw3<true>, dim3(ps.p[0].grid + ps.p[1].grid + ps.p[2].grid),
+                         dim3(kThreads), kLdsBytes, st, ps, rows);
     }
   }
   return check_launch();

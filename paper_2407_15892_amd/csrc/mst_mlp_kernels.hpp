@@ -220,14 +220,16 @@ struct DwProblem {
   float* dW;                     // [V][d]
 };
 struct DwProblems { DwProblem p[3]; };
-__global__ __launch_bounds__(kThreads) void k_mlp_dw3(DwProblems ps, int rows, int accumulate) {
+template <bool kStoreOnly>   // the first chunk only stores: the 16x16x32 tile; later chunks add to the stored sums
+__global__ __launch_bounds__(kThreads) void k_mlp_dw3(DwProblems ps, int rows) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   int b = blockIdx.x, which = 0;
   if (b >= ps.p[0].grid) { b -= ps.p[0].grid; which = 1; if (b >= ps.p[1].grid) { b -= ps.p[1].grid; which = 2; } }
   const DwProblem& q = ps.p[which];
   int vt, jt;
   if (!xcd_tile_2d(q.n_vt, q.n_jt, &vt, &jt, b)) return;
-  dw_tile(q.G, q.ldg, q.ldg, q.H, q.ldh, rows, q.d, q.V, vt, jt, accumulate, 1.0f, q.dW, q.d, smem);
+  if (kStoreOnly) dw_tile16(q.G, q.ldg, q.ldg, q.H, q.ldh, rows, q.d, q.V, vt, jt, 0, 1.0f, q.dW, q.d, smem);
+  else dw_tile(q.G, q.ldg, q.ldg, q.H, q.ldh, rows, q.d, q.V, vt, jt, 1, 1.0f, q.dW, q.d, smem);
 }
 
 }  // namespace mst
