@@ -170,6 +170,10 @@ struct PanelKS {
   static constexpr int SPW = NSLOT / C::kWaves;
   static_assert(NSLOT % C::kWaves == 0, "slots must divide over waves");
   static constexpr int kBytes = BK * RB;
+  // XOR swizzle of the 16-byte chunk index by the k row.  The two lane quarters served in one clock read the
+  // same 4 k rows, 32 bytes (2 chunks) apart in memory order: with a step of 4 chunks per row the 8 pieces of
+  // 32 bytes fall on 8 different bank groups (a step of 2 made row r of one quarter meet row r + 1 of the other).
+  static constexpr uint32_t kSwz = kPermute ? 2 : 4;
   __amdgpu_buffer_rsrc_t rsrc;
   uint32_t voff[SPW];
   uint32_t ok_mask, ld_bytes, slot0;
@@ -185,7 +189,7 @@ struct PanelKS {
 #pragma unroll
     for (int i = 0; i < SPW; ++i) {
       const uint32_t krow = RPS * (slot0 + i) + lane / CPR;
-      const uint32_t chunk = (lane % CPR) ^ (2 * (krow & 3));
+      const uint32_t chunk = (lane % CPR) ^ (kSwz * (krow & 3));
       voff[i] = krow * ld_bytes + chunk * 16;
       ok_mask |= ((chunk * 8) < cols_valid ? 1u : 0u) << i;
     }
@@ -195,7 +199,7 @@ struct PanelKS {
       const int m0 = 16 * (g & 1) + 4 * (i16 & 3);          // first of the 4 MFMA rows this lane's piece feeds
       const int col = wave_side_index * (32 * TILES) + 32 * t + a_row_of_mfma_row<kPermute>(m0);
       const int krow = 8 * (g >> 1) + (i16 >> 2);
-      rd[t] = krow * RB + (((col >> 3) ^ (2 * (i16 >> 2))) * 16) + (col & 7) * 2;
+      rd[t] = krow * RB + (((col >> 3) ^ (kSwz * (i16 >> 2))) * 16) + (col & 7) * 2;
     }
   }
   __device__ __forceinline__ void issue(uint32_t panel_lds, uint32_t k0) const {

@@ -126,7 +126,12 @@ struct PanelKS16 {
   // XOR swizzle of the 16-byte chunk index by the k row.  A quarter wave reads 4 k rows x 4 pieces of 8 bytes.
   // In memory order the 4 pieces of a row are 32 contiguous bytes (2 chunks), so rows must differ in chunk
   // bits 1-2; with the permutation the pieces are 64 bytes (4 chunks) apart, so rows must differ in bits 0-1.
-  __device__ __forceinline__ static uint32_t swz(uint32_t krow) { return kPermute ? (krow & 3) : 2 * (krow & 3); }
+  // The two lane quarters that are served in one clock read k rows 8 apart: in memory order bit 3 of the k row
+  // moves them to the other 128-byte half of the 256-byte bank window.  (With the permutation both quarters
+  // need the same 8-byte half of all 16 chunks of the window, which no 16-byte swizzle can separate.)
+  __device__ __forceinline__ static uint32_t swz(uint32_t krow) {
+    return kPermute ? (krow & 3) : (2 * (krow & 3)) ^ (8 * ((krow >> 3) & 1));
+  }
 
   __device__ __forceinline__ void init(const void* base, uint32_t ld_elems, uint32_t k_rows, uint32_t cols_valid,
                                        int wave, int lane, int wave_side_index) {
