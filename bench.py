@@ -28,13 +28,18 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 
 GEMM_KINDS = ("fwd_gemm_lse", "bwd_gemm_dlogits", "bwd_gemm_dh", "bwd_gemm_dw")
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command (see profiles/),
-# scaled by what the same counters read for a device copy of known size; keyed by (config, kernel kind).
+# Bytes fetched and written beyond L2 per launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command
+# (see profiles/), scaled by what the same counters read for a device copy of known size; keyed by
+# (config, backward schedule, kernel kind).  The forward does not depend on the schedule.
 PMC_TRAFFIC_BYTES = {
-    (2, "fwd_gemm_lse"): 1.689e9 + 0.004e9,
-    (2, "bwd_gemm_dlogits"): 1.760e9 + 0.264e9,
-    (2, "bwd_gemm_dh"): 1.581e9 + 0.068e9,
-    (2, "bwd_gemm_dw"): 4.855e9 + 2.101e9,
+    (2, "blocks", "fwd_gemm_lse"): 1.690e9 + 0.004e9,
+    (2, "blocks", "bwd_gemm_dlogits"): 1.659e9 + 0.266e9,
+    (2, "blocks", "bwd_gemm_dh"): 1.757e9 + 0.137e9,
+    (2, "blocks", "bwd_gemm_dw"): 1.631e9 + 0.284e9,
+    (2, "pairs", "fwd_gemm_lse"): 1.690e9 + 0.004e9,
+    (2, "pairs", "bwd_gemm_dlogits"): 1.760e9 + 0.264e9,
+    (2, "pairs", "bwd_gemm_dh"): 1.581e9 + 0.068e9,
+    (2, "pairs", "bwd_gemm_dw"): 4.855e9 + 2.101e9,
 }
 
 
@@ -86,11 +91,11 @@ MLP_FLOP_UNITS = {"gateup": 4.0, "down": 2.0, "da": 2.0, "gateup_bwd": 4.0, "dx"
 # HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of `bench.py --path mlp` (see profiles/)
 MLP_PMC_TRAFFIC_BYTES = {
     (2, "gateup"): 1.409e9 + 0.117e9,
-    (2, "down"): 0.705e9 + 0.035e9,
+    (2, "down"): 0.705e9 + 0.036e9,
     (2, "da"): 0.786e9 + 0.137e9,
     (2, "gateup_bwd"): 1.527e9 + 0.353e9,
     (2, "dx"): 1.414e9 + 0.040e9,
-    (2, "dw"): 3.252e9 + 0.705e9,
+    (2, "dw"): 3.475e9 + 0.776e9,
 }
 
 
@@ -320,7 +325,7 @@ def main() -> int:
         dom = max(GEMM_KINDS, key=lambda k: kern[k][0])
         ms, n = kern[dom]
         achieved = flop_per_launch(dom) / (ms / n * 1e-3) / 1e12
-        traffic = PMC_TRAFFIC_BYTES.get((args.config, dom))
+        traffic = PMC_TRAFFIC_BYTES.get((args.config, sched["schedule"], dom))
         roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
                     "flop_per_launch": flop_per_launch(dom), "avg_launch_ms": ms / n,
