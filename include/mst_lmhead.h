@@ -48,9 +48,10 @@
  *   - Arithmetic: bf16 operands, fp32 MFMA accumulation, fp32 log-sum-exp and
  *     softmax, dlogits = softmax - onehot rounded to bf16 (nearest even)
  *     before the two gradient GEMMs, grad_loss / N_valid applied in fp32 by
- *     their epilogues, dH rounded to bf16, dW fp32.  dW is accumulated over
- *     pairs of chunks in a fixed order without atomics: repeated calls give
- *     bit-identical dW.
+ *     their epilogues, dH rounded to bf16 (from fp32 sums), dW fp32.  What is
+ *     accumulated across launches (dW over blocks of rows, dH over windows of
+ *     the vocabulary or split partials) is summed in a fixed order without
+ *     atomics: repeated calls give bit-identical dW and dH.
  *   - N_valid == 0: loss = 0, dH = 0, dW = 0.
  */
 #ifndef MST_LMHEAD_H

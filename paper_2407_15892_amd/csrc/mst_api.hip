@@ -1,7 +1,9 @@
 // Host side of the mini-sequence LM-head + cross-entropy library: argument
 // validation, the chunk schedule over the M mini-sequences (Algorithm 2 lines
-// 1-3 and Algorithm 4 lines 1-4 of the paper: partition, then loop), workspace
-// carving, launches, and the optional per-kernel event timing.
+// 1-3 and Algorithm 4 lines 1-4 of the paper: partition, then loop; for the
+// backward also the choice between that loop and blocks of rows x vocabulary
+// windows of the same size), workspace carving, launches, and the optional
+// per-kernel event timing.
 #include "../../include/mst_lmhead.h"
 #include "host_util.hpp"
 #include "mst_kernels.hpp"

@@ -489,16 +489,17 @@ __global__ __launch_bounds__(256) void k_bwd_dh_reduce(const float* __restrict__
 }
 
 // ---------------------------------------------------------------------------
-// backward 3: dW (+)= G^T H over the rows of one or two consecutive chunks
+// backward 3: dW (+)= G^T H over the rows that are in the workspace (two consecutive chunks, or a
+// block of rows of one vocabulary window)
 //   A side = vocabulary (G columns, K-strided), B side = hidden index j (H columns, K-strided)
-//   dW is fp32 and is its own accumulator.  For every pass after the first the old dW tile is
-//   loaded straight into the MFMA accumulators before the main loop (the loads fly while the
-//   first operand panels arrive), the products are accumulated on top, and the tile is stored
-//   once: one read and one write of dW per pass and no extra registers.  Because dlogits is
-//   kept as bf16, two chunks fit where one chunk of fp32 logits would, so a pass covers two
-//   chunks and dW is read and written half as often as there are chunks.  The running sum is
-//   kept unscaled; the last pass multiplies by gamma = grad_loss / N_valid.  Passes run in order
-//   on one stream, so the summation order is fixed and dW is reproducible bit for bit.
+//   dW is fp32 and is its own accumulator.  For every pass over a part of dW after the first the
+//   old tile is loaded straight into the MFMA accumulators before the main loop, the products are
+//   accumulated on top, and the tile is stored once: one read and one write of dW per pass and no
+//   extra registers.  Because dlogits is kept as bf16, twice as many of them fit as fp32 logits
+//   would, so a pass covers two chunks (or, with a window of the vocabulary, many more rows) and dW
+//   is read and written correspondingly less often.  The running sum is kept unscaled; the last
+//   pass multiplies by gamma = grad_loss / N_valid.  Passes run in order on one stream, so the
+//   summation order is fixed and dW is reproducible bit for bit.
 //   The body is a device function so that the MLP path can serve its three weight gradients from one launch.
 // ---------------------------------------------------------------------------
 // G: [rows][ldg], columns [0, g_cols) readable (v < V of them used); Hc: [rows][ldh], columns [0, d) used;
