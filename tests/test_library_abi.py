@@ -158,3 +158,36 @@ def test_backward_schedule_choice_and_block_shapes(mst):
             mst.mst_set_bwd_schedule(7)
     finally:
         mst.mst_set_bwd_schedule(mst.BWD_SCHEDULE_AUTO)
+
+
+def test_block_shapes_fit_and_cover_for_random_shapes(mst):
+    """Host-only property test of the block schedule's shapes: whenever one is offered it covers S x V with whole
+    tiles, fits the reported workspace bytes together with the fp32 dH sums, and keeps 32-bit offsets in range."""
+    import random
+    rng = random.Random(20240715)
+    offered = 0
+    try:
+        mst.mst_set_bwd_schedule(mst.BWD_SCHEDULE_BLOCKS)
+        for _ in range(400):
+            d = 8 * rng.randint(1, 1024)
+            V = rng.randint(1, 300000)
+            S = rng.randint(1, 200000)
+            M = rng.randint(1, min(S, 256))
+            if mst.binding.mst_workspace_bytes_status(S, d, V, M) != 0:
+                continue
+            _, cap = mst.mst_workspace_bytes(S, d, V, M)
+            info = mst.mst_bwd_schedule_info(S, d, V, M)
+            C = -(-S // M)
+            if info["schedule"] != mst.BWD_SCHEDULE_BLOCKS:
+                assert info["rows_per_block"] == 2 * C and info["windows"] == 1
+                continue
+            offered += 1
+            R, Vw = info["rows_per_block"], info["vocab_per_window"]
+            assert R >= 256 and R % 256 == 0 and Vw >= 256 and Vw % 256 == 0
+            assert info["windows"] >= 2 and (info["windows"] - 1) * Vw < V <= info["windows"] * Vw
+            assert (info["row_blocks"] - 1) * R < S <= info["row_blocks"] * R
+            assert R * Vw * 2 + 256 + R * d * 4 <= cap, (S, d, V, M, info, cap)
+            assert R * Vw < 2 ** 30 and R * d < 2 ** 30
+        assert offered > 50
+    finally:
+        mst.mst_set_bwd_schedule(mst.BWD_SCHEDULE_AUTO)
