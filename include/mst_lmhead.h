@@ -34,7 +34,8 @@
  * Conventions
  *   - Every pointer named below is a DEVICE pointer owned by the caller, except
  *     where "host" is written.  The library allocates no device memory and
- *     keeps no state between calls (profiling events aside).
+ *     keeps no state between calls (profiling events and the backward-schedule
+ *     override of mst_set_bwd_schedule aside).
  *   - All work is enqueued on `stream` (a hipStream_t passed as void*); the
  *     calls return without waiting for the GPU.
  *   - Return value: MST_OK (0) or a negative error code.  Argument errors are
