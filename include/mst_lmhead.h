@@ -86,7 +86,11 @@ const char* mst_version(void);
 
 /*
  * Workspace sizes in bytes for the forward and the backward call (host-only,
- * launches nothing).  Either output pointer may be NULL.  The backward figure
+ * launches nothing).  Either output pointer may be NULL.  The forward figure
+ * is one (max, sum-exp) pair per row and 256-entry vocabulary tile for a group
+ * of consecutive mini-sequences (all of them unless that would exceed half a
+ * chunk of fp32 logits) plus 8 bytes per row: 33 MB at S = 8192, V = 128256.
+ * The backward figure
  * is for the case that `lse` and `n_valid` from the forward call are supplied:
  * two bf16 dlogits chunks, 2 * ceil(S/M) * (V rounded up to 8) * 2 bytes, which
  * for V % 8 == 0 is exactly one chunk of fp32 logits, ceil(S/M) * V * 4.

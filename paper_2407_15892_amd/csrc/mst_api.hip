@@ -29,6 +29,7 @@ struct Plan {
   int M;
   int C;            // rows per chunk = ceil(S / M)
   int n_chunks;     // non-empty chunks = ceil(S / C)
+  int64_t fwd_group_rows;   // rows whose log-sum-exp partials are merged by one launch: a whole number of chunks
   int ldg;          // leading dimension of the dlogits workspace (V rounded up to 8)
   int n_vt;         // vocabulary tiles
   int n_jt;         // hidden tiles
@@ -169,10 +170,20 @@ mst_status make_plan(int64_t S, int64_t d, int64_t V, int32_t M, Plan* p) {
   p->dh_ksteps = (ksteps + split - 1) / split;
   p->dh_split = (ksteps + p->dh_ksteps - 1) / p->dh_ksteps;
 
+  // Forward: one GEMM launch per mini-sequence; the (max, sum) pairs per row and vocabulary tile of a group of
+  // consecutive mini-sequences are merged by one launch.  A group is as many chunks as fit, with their pairs,
+  // into half of one fp32 logits chunk (all of them at the paper-shaped configurations).
+  {
+    const int64_t per_chunk = ((int64_t)p->n_vt * 8 + 4) * C;
+    int64_t g = (C * ldg * 2) / per_chunk;
+    if (g < 1) g = 1;
+    if (g > p->n_chunks) g = p->n_chunks;
+    p->fwd_group_rows = g * C;
+  }
   size_t off = sizeof(Control);
   p->f_nll = off;  off = align_up(off + (size_t)S * 4, 256);
-  p->f_tgt = off;  off = align_up(off + (size_t)C * 4, 256);
-  p->f_part = off; off = align_up(off + (size_t)p->n_vt * C * 8, 256);
+  p->f_tgt = off;  off = align_up(off + (size_t)p->fwd_group_rows * 4, 256);
+  p->f_part = off; off = align_up(off + (size_t)p->n_vt * p->fwd_group_rows * 8, 256);
   p->f_total = off;
 
   p->b_slot = (size_t)C * ldg * 2;
@@ -220,21 +231,22 @@ mst_status run_forward_chunks(const Plan& p, const __bf16* H, const __bf16* W, c
                               int ignore_index, char* ws, float* lse, float* nll, hipStream_t st) {
   float* tgt = reinterpret_cast<float*>(ws + p.f_tgt);
   float2* part = reinterpret_cast<float2*>(ws + p.f_part);
-  for (int i = 0; i < p.n_chunks; ++i) {
-    const int64_t r0 = (int64_t)i * p.C;
-    const int rows = (int)((p.S - r0) < p.C ? (p.S - r0) : p.C);
-    const int n_st = (rows + kTile - 1) / kTile;
-    const __bf16* Hc = H + r0 * p.d;
-    {
+  const size_t stride = (size_t)p.fwd_group_rows;
+  for (int64_t g0 = 0; g0 < p.S; g0 += p.fwd_group_rows) {
+    const int64_t g_rows = (p.S - g0) < p.fwd_group_rows ? (p.S - g0) : p.fwd_group_rows;
+    for (int64_t r0 = g0; r0 < g0 + g_rows; r0 += p.C) {
+      const int rows = (int)((p.S - r0) < p.C ? (p.S - r0) : p.C);
+      const int n_st = (rows + kTile - 1) / kTile;
       Scope sc(st, MST_K_FWD_GEMM_LSE);
       hipLaunchKernelGGL(k_fwd_gemm_lse, dim3(xcd_grid(n_st * p.n_vt)), dim3(kThreads), kLdsBytes, st,
-                         Hc, W, labels + r0, rows, (int)p.d, (int)p.V, n_st, p.n_vt, part, p.C, tgt);
+                         H + r0 * p.d, W, labels + r0, rows, (int)p.d, (int)p.V, n_st, p.n_vt,
+                         part + (r0 - g0), stride, tgt + (r0 - g0));
     }
     {
       Scope sc(st, MST_K_LSE_FINALIZE);
-      hipLaunchKernelGGL(k_lse_finalize, dim3((rows + kFinRows - 1) / kFinRows), dim3(kFinRows * kFinGroups), 0, st,
-                         part, p.C, p.n_vt, tgt, labels + r0, rows, (int)p.V, ignore_index,
-                         lse ? lse + r0 : nullptr, nll ? nll + r0 : nullptr);
+      hipLaunchKernelGGL(k_lse_finalize, dim3((unsigned)((g_rows + kFinRows - 1) / kFinRows)), dim3(kFinRows * kFinGroups), 0, st,
+                         part, stride, p.n_vt, tgt, labels + g0, (int)g_rows, (int)p.V, ignore_index,
+                         lse ? lse + g0 : nullptr, nll ? nll + g0 : nullptr);
     }
   }
   return check_launch();

@@ -175,7 +175,7 @@ __global__ __launch_bounds__(256) void k_shift_labels(const int* __restrict__ in
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void k_fwd_gemm_lse(
     const __bf16* __restrict__ Hc, const __bf16* __restrict__ W, const int* __restrict__ labels_c,
-    int rows, int d, int V, int n_st, int n_vt, float2* __restrict__ part, int part_stride,
+    int rows, int d, int V, int n_st, int n_vt, float2* __restrict__ part, size_t part_stride,
     float* __restrict__ tgt) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int w = xcd_work_item(n_st * n_vt);
@@ -275,7 +275,7 @@ __global__ __launch_bounds__(kThreads) void k_fwd_gemm_lse(
 constexpr int kFinRows = 64;
 constexpr int kFinGroups = 16;
 __global__ __launch_bounds__(kFinRows * kFinGroups) void k_lse_finalize(
-    const float2* __restrict__ part, int part_stride, int n_vt, const float* __restrict__ tgt,
+    const float2* __restrict__ part, size_t part_stride, int n_vt, const float* __restrict__ tgt,
     const int* __restrict__ labels_c, int rows, int V, int ignore_index,
     float* __restrict__ lse_c, float* __restrict__ nll_c) {
   __shared__ float2 sh[kFinGroups][kFinRows];
