@@ -26,7 +26,8 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 
-GEMM_KINDS = ("fwd_gemm_lse", "bwd_gemm_dlogits", "bwd_gemm_dh", "bwd_gemm_dw")
+# executed flop per step of each GEMM kernel kind, in units of S*d*V (a kind with no launches in a run is skipped)
+GEMM_KINDS = {"fwd_gemm_lse": 2.0, "bwd_gemm_dlogits": 2.0, "bwd_gemm_dh": 2.0, "bwd_gemm_dw": 2.0, "bwd_gemm_dh_dw": 4.0}
 
 # Bytes fetched and written beyond L2 per launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command
 # (see profiles/), scaled by what the same counters read for a device copy of known size; keyed by
@@ -225,7 +226,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--cpu-sample-rows", type=int, default=4096)
-    ap.add_argument("--bwd-schedule", choices=("auto", "pairs", "blocks"), default="auto",
+    ap.add_argument("--bwd-schedule", choices=("auto", "pairs", "blocks", "blocks_fused"), default="auto",
                     help="order of the LM-head backward pass (default: the library's own choice)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
@@ -251,10 +252,12 @@ def main() -> int:
         return 2
     mst.load_library()
     mst.mst_set_bwd_schedule({"auto": mst.BWD_SCHEDULE_AUTO, "pairs": mst.BWD_SCHEDULE_PAIRS,
-                              "blocks": mst.BWD_SCHEDULE_BLOCKS}[args.bwd_schedule])
+                              "blocks": mst.BWD_SCHEDULE_BLOCKS,
+                              "blocks_fused": mst.BWD_SCHEDULE_BLOCKS_FUSED}[args.bwd_schedule])
     cfg = mi.CONFIGS[args.config]
     sched = mst.mst_bwd_schedule_info(cfg.S, cfg.d, cfg.V, cfg.M)
-    sched["schedule"] = {mst.BWD_SCHEDULE_PAIRS: "pairs", mst.BWD_SCHEDULE_BLOCKS: "blocks"}[sched["schedule"]]
+    sched["schedule"] = {mst.BWD_SCHEDULE_PAIRS: "pairs", mst.BWD_SCHEDULE_BLOCKS: "blocks",
+                         mst.BWD_SCHEDULE_BLOCKS_FUSED: "blocks_fused"}[sched["schedule"]]
     t0 = time.perf_counter()
     inp = mi.make_inputs(cfg)
     gen_s = time.perf_counter() - t0
@@ -319,10 +322,10 @@ def main() -> int:
         for k, (ms, n) in kern.items():
             if n:
                 kernels[k] = {"launches": n, "avg_ms": ms / n, "total_ms_per_step": ms / args.steps}
-        # every GEMM kind executes 2*S*d*V flop per step in total, split over its launches of that step
+        # a GEMM kind executes GEMM_KINDS[kind] * S*d*V flop per step in total, split over its launches of that step
         def flop_per_launch(kind):
-            return 2.0 * S * d * V / (kern[kind][1] / args.steps)
-        dom = max(GEMM_KINDS, key=lambda k: kern[k][0])
+            return GEMM_KINDS[kind] * S * d * V / (kern[kind][1] / args.steps)
+        dom = max(GEMM_KINDS, key=lambda k: kern.get(k, (0.0, 0))[0])
         ms, n = kern[dom]
         achieved = flop_per_launch(dom) / (ms / n * 1e-3) / 1e12
         traffic = PMC_TRAFFIC_BYTES.get((args.config, sched["schedule"], dom))
@@ -340,7 +343,7 @@ def main() -> int:
                                     "achieved_GBs": alg_bytes / (ms / n * 1e-3) / 1e9, "peak_GBs": PEAK_HBM_GBS,
                                     "frac": alg_bytes / (ms / n * 1e-3) / 1e9 / PEAK_HBM_GBS}
         for k in GEMM_KINDS:
-            ms_k, n_k = kern[k]
+            ms_k, n_k = kern.get(k, (0.0, 0))
             if n_k:
                 kernels[k]["tflops"] = flop_per_launch(k) / (ms_k / n_k * 1e-3) / 1e12
 

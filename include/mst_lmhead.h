@@ -178,14 +178,17 @@ mst_status mst_lmhead_ce_bwd(const void* H, const void* W, const int32_t* labels
  *   MST_BWD_SCHEDULE_BLOCKS  the same bytes hold R rows by one window of the vocabulary (plus fp32 dH sums
  *                            of the R rows), R as large as fits: dW of a window accumulates over the row
  *                            blocks (no re-read at all when R covers S), dH of a row block over the windows.
+ *   MST_BWD_SCHEDULE_BLOCKS_FUSED  the block order with the dH and the dW GEMM of each (row block, window)
+ *                            in one launch: their tile spaces then share one partly filled last round of
+ *                            workgroups instead of leaving one each (same arithmetic as BLOCKS, bit for bit).
  *   MST_BWD_SCHEDULE_AUTO    (default) whichever a host-side cost model (rounds of workgroups plus fp32
  *                            gradient traffic) ranks faster for the shape.
  * mst_set_bwd_schedule: host, process-wide, takes effect at the next call; MST_ERR_BAD_SHAPE for an unknown
  * value.  mst_bwd_schedule_info: host, pure; fills info[0..7] = {schedule that would run, rows per block,
  * row blocks, vocabulary entries per window, windows, dH split count, cost estimate of PAIRS in us, of
- * BLOCKS in us (0 if no block shape fits)}.
+ * the block order that would be chosen in us (0 if no block shape fits)}.
  */
-enum { MST_BWD_SCHEDULE_AUTO = 0, MST_BWD_SCHEDULE_PAIRS = 1, MST_BWD_SCHEDULE_BLOCKS = 2 };
+enum { MST_BWD_SCHEDULE_AUTO = 0, MST_BWD_SCHEDULE_PAIRS = 1, MST_BWD_SCHEDULE_BLOCKS = 2, MST_BWD_SCHEDULE_BLOCKS_FUSED = 3 };
 mst_status mst_set_bwd_schedule(int32_t schedule);
 mst_status mst_bwd_schedule_info(int64_t S, int64_t d, int64_t V, int32_t M, int64_t* info);
 
@@ -218,6 +221,7 @@ enum {
   MST_K_BWD_GEMM_DH,     /* dH_i = dlogits_i W (split over V)                   */
   MST_K_BWD_DH_REDUCE,   /* fixed-order sum of the dH split partials            */
   MST_K_BWD_GEMM_DW,     /* dW += dlogits_i^T H_i                               */
+  MST_K_BWD_GEMM_DH_DW,  /* both of the above for one block, from one launch    */
   MST_PROFILE_KINDS
 };
 mst_status mst_profile_enable(int enable);

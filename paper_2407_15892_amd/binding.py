@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libmst_lmhead.so")
 
 MST_OK = 0
-PROFILE_KINDS = 8
+PROFILE_KINDS = 9     # MST_PROFILE_KINDS of include/mst_lmhead.h (checked against the library by the tests)
 
 _lib = None
 
@@ -157,7 +157,7 @@ def mst_lmhead_ce_bwd(H, W, labels, ignore_index: int, M: int, grad_loss: float,
         _ptr(dH), _ptr(dW), _stream_handle(stream)))
 
 
-BWD_SCHEDULE_AUTO, BWD_SCHEDULE_PAIRS, BWD_SCHEDULE_BLOCKS = 0, 1, 2
+BWD_SCHEDULE_AUTO, BWD_SCHEDULE_PAIRS, BWD_SCHEDULE_BLOCKS, BWD_SCHEDULE_BLOCKS_FUSED = 0, 1, 2, 3
 
 
 def mst_set_bwd_schedule(schedule: int) -> None:

@@ -49,6 +49,7 @@ struct Plan {
   // by blk_win_tiles * kTile vocabulary entries (bf16, leading dimension blk_ldg) and, behind it, fp32 dH sums of
   // blk_rows x d.  blk_n_rb row blocks x blk_n_win vocabulary windows cover S x V.
   bool blk_use;
+  bool blk_fused;     // dH and dW of a block from one launch
   int blk_rows, blk_n_rb, blk_win_tiles, blk_n_win, blk_ldg;
   size_t blk_acc;     // byte offset of the dH sums
   double est_pairs_us, est_blocks_us;   // the cost model's figures (for the record; see choose_schedule)
@@ -68,6 +69,7 @@ struct Plan {
 // gradient traffic at a nominal bandwidth; it only has to rank the candidates.
 constexpr double kUsPerKStep = 1.5;      // one 256 x 256 x 64 block-tile step with one workgroup per CU
 constexpr double kRmwBytesPerUs = 4.0e6; // fp32 read-modify-write streams next to a running GEMM
+constexpr double kFuseWaste = 0.0125;     // idle share of separate dH and dW launches from which one launch serves both
 double rounds_us(int64_t tiles, int64_t k) {
   return (double)((tiles + kNumCu - 1) / kNumCu) * (double)((k + kBK - 1) / kBK) * kUsPerKStep;
 }
@@ -93,6 +95,7 @@ void choose_schedule(Plan* p) {
   p->est_pairs_us = pairs;
   // blocks: for every window count, the largest row block that fits, then rows balanced over the blocks
   p->blk_use = false;
+  p->blk_fused = false;
   p->est_blocks_us = 0.0;
   double best = 0.0;
   for (int n_win = 2; n_win <= kMaxWindows && n_win <= n_vt; ++n_win) {
@@ -108,7 +111,7 @@ void choose_schedule(Plan* p) {
     const int n_rb = (int)((S + R - 1) / R);
     R = ((S + n_rb - 1) / n_rb + kTile - 1) / kTile * kTile;
     if (R * ldg_w >= (int64_t(1) << 30) || R * d >= (int64_t(1) << 30)) continue;   // 32-bit offsets inside a block
-    double t = 0.0;
+    double t = 0.0, sep_us = 0.0, work_us = 0.0;
     for (int rb = 0; rb < n_rb; ++rb) {
       const int64_t rows = (S - rb * R) < R ? (S - rb * R) : R;
       const int64_t n_st = (rows + kTile - 1) / kTile;
@@ -116,15 +119,28 @@ void choose_schedule(Plan* p) {
         const int64_t tiles_w = (w + 1) * win_tiles <= n_vt ? win_tiles : n_vt - w * win_tiles;
         const int64_t cols = tiles_w * kTile < V - (int64_t)w * ldg_w ? tiles_w * kTile : V - (int64_t)w * ldg_w;
         t += rounds_us(n_st * tiles_w, d);                                                 // dlogits
-        t += rounds_us(n_st * n_jt, cols);                                                 // dH
         t += (double)((w > 0 ? 4 : 0) + (w + 1 < n_win ? 4 : 2)) * (double)(rows * d) / kRmwBytesPerUs;
-        t += rounds_us(tiles_w * n_jt, rows);                                              // dW
         t += (double)((rb > 0 ? 8 : 4) * cols * d) / kRmwBytesPerUs;
+        const double dh_dw = rounds_us(n_st * n_jt, cols) + rounds_us(tiles_w * n_jt, rows);  // two launches
+        t += dh_dw;
+        sep_us += dh_dw;
+        work_us += ((double)(n_st * n_jt) * (double)((cols + kBK - 1) / kBK) +
+                    (double)(tiles_w * n_jt) * (double)((rows + kBK - 1) / kBK)) / kNumCu * kUsPerKStep;
       }
     }
-    if (!p->blk_use || t < best) {
-      best = t;
+    // One launch for the dH and the dW tiles of a block: a partly filled last round of dH workgroups is topped up
+    // with dW tiles, and one launch boundary per block goes away.  Measured: no difference where both tile counts
+    // fill whole rounds anyway (config 2: 512 and 1008 tiles), -1.5 to -2 % of the step where they do not (Gemma
+    // shape: 896 dH tiles = 3.5 rounds; config 5: 496).  It is used when the two separate launches would leave at
+    // least kFuseWaste of their CU time idle; the block shapes are ranked without it.
+    const int forced_now = g_bwd_schedule.load();
+    const bool fuse = forced_now == MST_BWD_SCHEDULE_BLOCKS_FUSED ||
+                      (forced_now == MST_BWD_SCHEDULE_AUTO && sep_us - work_us >= kFuseWaste * sep_us);
+    const double t_pick = t;
+    if (!p->blk_use || t_pick < best) {
+      best = t_pick;
       p->blk_use = true;
+      p->blk_fused = fuse;
       p->blk_rows = (int)R; p->blk_n_rb = n_rb; p->blk_win_tiles = win_tiles; p->blk_n_win = n_win;
       p->blk_ldg = (int)ldg_w;
       p->blk_acc = align_up((size_t)R * ldg_w * 2, 256);
@@ -134,7 +150,7 @@ void choose_schedule(Plan* p) {
   const int forced = g_bwd_schedule.load();
   if (forced == MST_BWD_SCHEDULE_PAIRS) p->blk_use = false;
   else if (forced == MST_BWD_SCHEDULE_AUTO && p->blk_use && !(best < pairs)) p->blk_use = false;
-  // MST_BWD_SCHEDULE_BLOCKS keeps the best block shape whenever one fits
+  // MST_BWD_SCHEDULE_BLOCKS and _BLOCKS_FUSED keep the best block shape whenever one fits
 }
 
 mst_status make_plan(int64_t S, int64_t d, int64_t V, int32_t M, Plan* p) {
@@ -214,6 +230,8 @@ void set_kernel_attributes() {
   set((const void*)k_bwd_gemm_dh);
   set((const void*)k_bwd_gemm_dw<false>);
   set((const void*)k_bwd_gemm_dw<true>);
+  set((const void*)k_bwd_gemm_dh_dw<false>);
+  set((const void*)k_bwd_gemm_dh_dw<true>);
 }
 
 mst_status check_launch() { return hipGetLastError() == hipSuccess ? MST_OK : MST_ERR_LAUNCH; }
@@ -437,19 +455,30 @@ mst_status mst_lmhead_ce_bwd(const void* H, const void* W, const int32_t* labels
                              Hb + r0 * p.d, Wb + v_base * p.d, labels + r0, lse + r0, rows, (int)p.d, Vw, (int)v_base,
                              (int)p.V, ignore_index, n_st, tiles_w, G, p.blk_ldg);
         }
-        {
-          Scope sc(st, MST_K_BWD_GEMM_DH);
-          const int mode = w == 0 ? kDhFirst : (w == p.blk_n_win - 1 ? kDhLast : kDhAdd);
-          hipLaunchKernelGGL(k_bwd_gemm_dh, dim3(xcd_grid_2d(n_st, p.n_jt)), dim3(kThreads), kLdsBytes, st,
-                             G, p.blk_ldg, Wb + v_base * p.d, rows, (int)p.d, Vw, n_st, p.n_jt, 1, (Vw + kBK - 1) / kBK, mode,
-                             nv, grad_loss, dh_sums, p.blk_rows, dHb + r0 * p.d);
-        }
-        {
-          Scope sc(st, MST_K_BWD_GEMM_DW);
-          hipLaunchKernelGGL(rb > 0 ? k_bwd_gemm_dw<false> : k_bwd_gemm_dw<true>, dim3(xcd_grid_2d(tiles_w, p.n_jt)),
-                             dim3(kThreads), kLdsBytes, st,
-                             G, p.blk_ldg, Hb + r0 * p.d, rows, (int)p.d, Vw, tiles_w, p.n_jt,
-                             rb == p.blk_n_rb - 1 ? 1 : 0, nv, grad_loss, dW + v_base * p.d);
+        const int mode = w == 0 ? kDhFirst : (w == p.blk_n_win - 1 ? kDhLast : kDhAdd);
+        const int dw_last = rb == p.blk_n_rb - 1 ? 1 : 0;
+        if (p.blk_fused) {
+          Scope sc(st, MST_K_BWD_GEMM_DH_DW);
+          const int dh_grid = xcd_grid_2d(n_st, p.n_jt);
+          hipLaunchKernelGGL(rb > 0 ? k_bwd_gemm_dh_dw<false> : k_bwd_gemm_dh_dw<true>,
+                             dim3(dh_grid + xcd_grid_2d(tiles_w, p.n_jt)), dim3(kThreads), kLdsBytes, st,
+                             G, p.blk_ldg, Wb + v_base * p.d, Hb + r0 * p.d, rows, (int)p.d, Vw, n_st, tiles_w, p.n_jt,
+                             dh_grid, mode, dw_last, nv, grad_loss, dh_sums, p.blk_rows, dHb + r0 * p.d,
+                             dW + v_base * p.d);
+        } else {
+          {
+            Scope sc(st, MST_K_BWD_GEMM_DH);
+            hipLaunchKernelGGL(k_bwd_gemm_dh, dim3(xcd_grid_2d(n_st, p.n_jt)), dim3(kThreads), kLdsBytes, st,
+                               G, p.blk_ldg, Wb + v_base * p.d, rows, (int)p.d, Vw, n_st, p.n_jt, 1, (Vw + kBK - 1) / kBK, mode,
+                               nv, grad_loss, dh_sums, p.blk_rows, dHb + r0 * p.d);
+          }
+          {
+            Scope sc(st, MST_K_BWD_GEMM_DW);
+            hipLaunchKernelGGL(rb > 0 ? k_bwd_gemm_dw<false> : k_bwd_gemm_dw<true>, dim3(xcd_grid_2d(tiles_w, p.n_jt)),
+                               dim3(kThreads), kLdsBytes, st,
+                               G, p.blk_ldg, Hb + r0 * p.d, rows, (int)p.d, Vw, tiles_w, p.n_jt,
+                               dw_last, nv, grad_loss, dW + v_base * p.d);
+          }
         }
       }
     }
@@ -475,8 +504,7 @@ mst_status mst_lmhead_ce_bwd(const void* H, const void* W, const int32_t* labels
 }
 
 mst_status mst_set_bwd_schedule(int32_t schedule) {
-  if (schedule != MST_BWD_SCHEDULE_AUTO && schedule != MST_BWD_SCHEDULE_PAIRS && schedule != MST_BWD_SCHEDULE_BLOCKS)
-    return MST_ERR_BAD_SHAPE;
+  if (schedule < MST_BWD_SCHEDULE_AUTO || schedule > MST_BWD_SCHEDULE_BLOCKS_FUSED) return MST_ERR_BAD_SHAPE;
   g_bwd_schedule.store(schedule);
   return MST_OK;
 }
@@ -486,7 +514,7 @@ mst_status mst_bwd_schedule_info(int64_t S, int64_t d, int64_t V, int32_t M, int
   Plan p;
   const mst_status s = make_plan(S, d, V, M, &p);
   if (s != MST_OK) return s;
-  info[0] = p.blk_use ? MST_BWD_SCHEDULE_BLOCKS : MST_BWD_SCHEDULE_PAIRS;
+  info[0] = p.blk_use ? (p.blk_fused ? MST_BWD_SCHEDULE_BLOCKS_FUSED : MST_BWD_SCHEDULE_BLOCKS) : MST_BWD_SCHEDULE_PAIRS;
   info[1] = p.blk_use ? p.blk_rows : 2 * (int64_t)p.C;
   info[2] = p.blk_use ? p.blk_n_rb : (p.n_chunks + 1) / 2;
   info[3] = p.blk_use ? (int64_t)p.blk_win_tiles * kTile : p.V;
@@ -509,7 +537,7 @@ mst_status mst_profile_collect(double* ms_per_kind, int64_t* launches_per_kind) 
 const char* mst_profile_kind_name(int kind) {
   static const char* names[MST_PROFILE_KINDS] = {
       "label_scan", "fwd_gemm_lse", "lse_finalize", "loss_reduce",
-      "bwd_gemm_dlogits", "bwd_gemm_dh", "bwd_dh_reduce", "bwd_gemm_dw"};
+      "bwd_gemm_dlogits", "bwd_gemm_dh", "bwd_dh_reduce", "bwd_gemm_dw", "bwd_gemm_dh_dw"};
   return (kind >= 0 && kind < MST_PROFILE_KINDS) ? names[kind] : "?";
 }
 

@@ -398,21 +398,22 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dlogits(
 //             to them, the last adds and writes gamma * total as bf16.  Launches run in order on one stream, so
 //             the summation order is fixed.
 constexpr int kDhSplit = 0, kDhFirst = 1, kDhAdd = 2, kDhLast = 3;
-__global__ __launch_bounds__(kThreads) void k_bwd_gemm_dh(
+// The body is a device function (block = index of the workgroup within this kernel's tile space) so that a
+// launch can serve the dH and the dW tiles of a vocabulary window together.
+__device__ __forceinline__ void dh_tile(
     const __bf16* __restrict__ G, int ldg, const __bf16* __restrict__ W, int rows, int d, int V,
     int n_st, int n_jt, int n_split, int ksteps_per_split, int mode,
     const long long* __restrict__ n_valid, float grad_loss,
     float* __restrict__ partial /* [n_split][rows_stride][d] */, int rows_stride,
-    __bf16* __restrict__ dHc /* written by kDhSplit with n_split == 1 and by kDhLast */) {
-  extern __shared__ __attribute__((aligned(1024))) char smem[];
+    __bf16* __restrict__ dHc /* written by kDhSplit with n_split == 1 and by kDhLast */, int block, char* smem) {
   int st, jt, sp = 0;
   if (mode == kDhSplit) {
-    const int w = xcd_work_item(n_st * n_jt * n_split);
+    const int w = xcd_work_item(n_st * n_jt * n_split);   // not combined with other tile spaces: uses blockIdx.x
     if (w < 0) return;
     st = w % n_st;
     jt = (w / n_st) % n_jt;
     sp = w / (n_st * n_jt);
-  } else if (!xcd_tile_2d(n_st, n_jt, &st, &jt)) {   // many row tiles: rectangles of row x hidden tiles per XCD
+  } else if (!xcd_tile_2d(n_st, n_jt, &st, &jt, block)) {   // many row tiles: rectangles of row x hidden tiles per XCD
     return;
   }
   const int s0 = st * kTile, j0 = jt * kTile;
@@ -464,6 +465,16 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dh(
         }
       }
     }
+}
+
+__global__ __launch_bounds__(kThreads) void k_bwd_gemm_dh(
+    const __bf16* __restrict__ G, int ldg, const __bf16* __restrict__ W, int rows, int d, int V,
+    int n_st, int n_jt, int n_split, int ksteps_per_split, int mode,
+    const long long* __restrict__ n_valid, float grad_loss,
+    float* __restrict__ partial, int rows_stride, __bf16* __restrict__ dHc) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  dh_tile(G, ldg, W, rows, d, V, n_st, n_jt, n_split, ksteps_per_split, mode, n_valid, grad_loss, partial, rows_stride,
+          dHc, blockIdx.x, smem);
 }
 
 // fixed-order sum over the splits, scale by gamma, round to bf16.  8 outputs per thread.
@@ -639,6 +650,31 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dw(
   int vt, jt;
   if (!xcd_tile_2d(n_vt, n_jt, &vt, &jt)) return;
   const float scale = last ? gamma_of(n_valid, grad_loss) : 1.0f;
+  if (kStoreOnly) dw_tile16(G, ldg, ldg, Hc, d, rows, d, V, vt, jt, 0, scale, dW, d, smem);
+  else dw_tile(G, ldg, ldg, Hc, d, rows, d, V, vt, jt, 1, scale, dW, d, smem);
+}
+
+// dH and dW of one (row block, vocabulary window) from one launch: both read the same dlogits block and
+// neither depends on the other.  The first dh_grid workgroups take the dH tiles (the longer ones: their
+// contraction runs over the window, dW's over the rows), the rest the dW tiles; with one workgroup per CU the
+// hardware hands out tiles as CUs become free, so the two tile spaces share one partly filled last round
+// instead of leaving one each.  dh_grid = xcd_grid_2d(n_st, n_jt), a multiple of the XCD count, so both tile
+// spaces keep their XCD-aware mapping.
+template <bool kStoreOnly>
+__global__ __launch_bounds__(kThreads) void k_bwd_gemm_dh_dw(
+    const __bf16* __restrict__ G, int ldg, const __bf16* __restrict__ W, const __bf16* __restrict__ Hc,
+    int rows, int d, int V, int n_st, int n_vt, int n_jt, int dh_grid, int dh_mode, int dw_last,
+    const long long* __restrict__ n_valid, float grad_loss,
+    float* __restrict__ dh_sums, int rows_stride, __bf16* __restrict__ dHc, float* __restrict__ dW) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  if ((int)blockIdx.x < dh_grid) {
+    dh_tile(G, ldg, W, rows, d, V, n_st, n_jt, 1, (V + kBK - 1) / kBK, dh_mode, n_valid, grad_loss, dh_sums, rows_stride,
+            dHc, blockIdx.x, smem);
+    return;
+  }
+  int vt, jt;
+  if (!xcd_tile_2d(n_vt, n_jt, &vt, &jt, (int)blockIdx.x - dh_grid)) return;
+  const float scale = dw_last ? gamma_of(n_valid, grad_loss) : 1.0f;
   if (kStoreOnly) dw_tile16(G, ldg, ldg, Hc, d, rows, d, V, vt, jt, 0, scale, dW, d, smem);
   else dw_tile(G, ldg, ldg, Hc, d, rows, d, V, vt, jt, 1, scale, dW, d, smem);
 }

@@ -81,7 +81,7 @@ def test_fullsize_config_matches_oracle_on_samples(cfg_index):
     # --- the other order of the backward pass against the same references
     import paper_2407_15892_amd as mst
     chosen = mst.mst_bwd_schedule_info(cfg.S, cfg.d, cfg.V, cfg.M)
-    other = mst.BWD_SCHEDULE_PAIRS if chosen["schedule"] == mst.BWD_SCHEDULE_BLOCKS else mst.BWD_SCHEDULE_BLOCKS
+    other = mst.BWD_SCHEDULE_BLOCKS if chosen["schedule"] == mst.BWD_SCHEDULE_PAIRS else mst.BWD_SCHEDULE_PAIRS
     try:
         mst.mst_set_bwd_schedule(other)
         forced = mst.mst_bwd_schedule_info(cfg.S, cfg.d, cfg.V, cfg.M)

@@ -90,7 +90,7 @@ def test_null_and_workspace_errors_come_before_any_launch(mst):
 def test_profile_kind_names(mst):
     lib = mst.load_library()
     names = [lib.mst_profile_kind_name(i).decode() for i in range(mst.binding.PROFILE_KINDS)]
-    assert names[1] == "fwd_gemm_lse" and names[-1] == "bwd_gemm_dw" and len(set(names)) == len(names)
+    assert names[1] == "fwd_gemm_lse" and names[-1] == "bwd_gemm_dh_dw" and len(set(names)) == len(names)
 
 
 def test_chunk_count_policy(mst):
@@ -141,6 +141,10 @@ def test_backward_schedule_choice_and_block_shapes(mst):
             assert pairs["rows_per_block"] == 2 * cfg.C and pairs["windows"] == 1 and pairs["vocab_per_window"] == cfg.V
             mst.mst_set_bwd_schedule(mst.BWD_SCHEDULE_BLOCKS)
             blocks = mst.mst_bwd_schedule_info(cfg.S, cfg.d, cfg.V, cfg.M)
+            assert blocks["schedule"] in (mst.BWD_SCHEDULE_BLOCKS, mst.BWD_SCHEDULE_PAIRS)   # never fused unless asked
+            mst.mst_set_bwd_schedule(mst.BWD_SCHEDULE_BLOCKS_FUSED)
+            fused = mst.mst_bwd_schedule_info(cfg.S, cfg.d, cfg.V, cfg.M)
+            assert fused["schedule"] in (mst.BWD_SCHEDULE_BLOCKS_FUSED, mst.BWD_SCHEDULE_PAIRS)
             if blocks["schedule"] == mst.BWD_SCHEDULE_BLOCKS:
                 R, Vw = blocks["rows_per_block"], blocks["vocab_per_window"]
                 assert R % 256 == 0 and Vw % 256 == 0 and blocks["windows"] >= 2
@@ -148,11 +152,15 @@ def test_backward_schedule_choice_and_block_shapes(mst):
                 # dlogits of the block (bf16) and the fp32 dH sums of its rows fit the same bytes
                 assert R * Vw * 2 + R * cfg.d * 4 + 256 <= cap, (cfg.name, blocks, cap)
             # the automatic choice is the cheaper estimate
-            want = mst.BWD_SCHEDULE_BLOCKS if 0 < auto["est_blocks_us"] < auto["est_pairs_us"] else mst.BWD_SCHEDULE_PAIRS
-            assert auto["schedule"] == want, (cfg.name, auto)
+            if 0 < auto["est_blocks_us"] < auto["est_pairs_us"]:
+                assert auto["schedule"] in (mst.BWD_SCHEDULE_BLOCKS, mst.BWD_SCHEDULE_BLOCKS_FUSED), (cfg.name, auto)
+            else:
+                assert auto["schedule"] == mst.BWD_SCHEDULE_PAIRS, (cfg.name, auto)
         # large vocabulary, short chunks: blocks; tiny problems: pairs
         mst.mst_set_bwd_schedule(mst.BWD_SCHEDULE_AUTO)
         assert mst.mst_bwd_schedule_info(8192, 4096, 128256, 8)["schedule"] == mst.BWD_SCHEDULE_BLOCKS
+        # 64 x 14 dH tiles leave half a round of workgroups idle: dH and dW share a launch
+        assert mst.mst_bwd_schedule_info(16384, 3584, 256000, 16)["schedule"] == mst.BWD_SCHEDULE_BLOCKS_FUSED
         assert mst.mst_bwd_schedule_info(512, 256, 4096, 4)["schedule"] == mst.BWD_SCHEDULE_PAIRS
         with pytest.raises(mst.MstError):
             mst.mst_set_bwd_schedule(7)
@@ -178,9 +186,10 @@ def test_block_shapes_fit_and_cover_for_random_shapes(mst):
             _, cap = mst.mst_workspace_bytes(S, d, V, M)
             info = mst.mst_bwd_schedule_info(S, d, V, M)
             C = -(-S // M)
-            if info["schedule"] != mst.BWD_SCHEDULE_BLOCKS:
+            if info["schedule"] == mst.BWD_SCHEDULE_PAIRS:
                 assert info["rows_per_block"] == 2 * C and info["windows"] == 1
                 continue
+            assert info["schedule"] == mst.BWD_SCHEDULE_BLOCKS
             offered += 1
             R, Vw = info["rows_per_block"], info["vocab_per_window"]
             assert R >= 256 and R % 256 == 0 and Vw >= 256 and Vw % 256 == 0
@@ -191,3 +200,15 @@ def test_block_shapes_fit_and_cover_for_random_shapes(mst):
         assert offered > 50
     finally:
         mst.mst_set_bwd_schedule(mst.BWD_SCHEDULE_AUTO)
+
+
+def test_profile_kind_count_matches_the_library(mst):
+    """mst_profile_collect fills MST_PROFILE_KINDS entries: the binding's array length has to be that number."""
+    lib = mst.load_library()
+    names = []
+    while lib.mst_profile_kind_name(len(names)).decode() != "?":
+        names.append(lib.mst_profile_kind_name(len(names)).decode())
+    assert len(names) == mst.binding.PROFILE_KINDS, names
+    header = open(os.path.join(os.path.dirname(__file__), "..", "include", "mst_lmhead.h")).read()
+    enum = header[header.index("MST_K_LABEL_SCAN = 0"):header.index("MST_PROFILE_KINDS\n")]
+    assert enum.count("MST_K_") == len(names)
