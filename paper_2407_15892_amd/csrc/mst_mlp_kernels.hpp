@@ -122,25 +122,39 @@ __global__ __launch_bounds__(kThreads) void k_mlp_gateup(
   }
 }
 
-// epilogue of the two plain GEMMs: a lane holds, for each of its rows s, 32 consecutive n (A side, permuted):
-// four 16-byte bf16 stores per row
+// epilogue of the two plain GEMMs: a lane holds, for each of its rows s, 32 consecutive n (A side, permuted),
+// i.e. 64 contiguous bytes of bf16, and the lanes of a wave instruction hold 16 different rows.  Stored directly,
+// every instruction would be 64 separate 16-byte writes; instead the bf16 tile is staged in LDS (free after the main
+// loop; rows padded by 16 bytes, which spreads the 16 rows of a quarter wave over all banks) and every wave
+// instruction then writes two whole rows of the tile.
 template <class T>
 __device__ __forceinline__ void store_rows_bf16(const f32x4 (&acc)[T::TA][T::TB], __bf16* __restrict__ out, int ldo,
-                                                int rows, int N, int s0, int n0, int wa, int wb, int lane) {
-  static_assert(T::TA == 8, "one 128-wide permuted block per wave row");
-  const int nb = n0 + wa * 128 + 32 * (lane >> 4);
+                                                int rows, int N, int s0, int n0, int wa, int wb, int wave, int lane,
+                                                char* smem) {
+  static_assert(T::TA == 8 && T::EA == 256, "one 128-wide permuted block per wave row, two wave rows");
+  constexpr int kStageRow = T::EA * 2 + 16;
 #pragma unroll
   for (int u = 0; u < T::TB; ++u) {
-    const int s_local = s0 + wb * (16 * T::TB) + 16 * u + (lane & 15);
-    if (s_local >= rows) continue;
-    __bf16* orow = out + (size_t)s_local * ldo;
+    const int row = wb * (16 * T::TB) + 16 * u + (lane & 15);
+    char* srow = smem + row * kStageRow + (wa * 128 + 32 * (lane >> 4)) * 2;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {                    // tiles 2p and 2p + 1: n = nb + 8p .. + 7
       bf16x8 o;
 #pragma unroll
       for (int e = 0; e < 8; ++e) o[e] = (__bf16)acc[2 * p + (e >> 2)][u][e & 3];
-      if (nb + 8 * p < N) *reinterpret_cast<bf16x8*>(orow + nb + 8 * p) = o;      // N % 8 == 0
+      *reinterpret_cast<bf16x8*>(srow + 16 * p) = o;
     }
+  }
+  __syncthreads();
+  const int col = (lane & 31) * 8;                   // 8 entries = 16 bytes per lane, 32 lanes per row
+  const bool col_ok = n0 + col < N;                  // N % 8 == 0
+  constexpr int kRowsPerWave = T::EB / T::kWaves;
+#pragma unroll
+  for (int i = 0; i < kRowsPerWave / 2; ++i) {
+    const int row = kRowsPerWave * wave + 2 * i + (lane >> 5);
+    if (s0 + row < rows && col_ok)
+      *reinterpret_cast<bf16x8*>(out + (size_t)(s0 + row) * ldo + n0 + col) =
+          *reinterpret_cast<const bf16x8*>(smem + row * kStageRow + col * 2);
   }
 }
 
@@ -166,7 +180,7 @@ __global__ __launch_bounds__(kThreads) void k_mlp_gemm_nt(
   pa.init(Q + (size_t)n0 * ldq, ldq, N - n0, K, wave, lane, wa);
   pb.init(P + (size_t)s0 * ldp, ldp, rows - s0, K, wave, lane, wb);
   gemm_mainloop_pp<Tile16>(acc, pa, pb, smem, 0, K, wa);
-  store_rows_bf16<Tile16>(acc, out, ldo, rows, N, s0, n0, wa, wb, lane);
+  store_rows_bf16<Tile16>(acc, out, ldo, rows, N, s0, n0, wa, wb, wave, lane, smem);
 }
 
 // ---------------------------------------------------------------------------
@@ -204,7 +218,7 @@ __global__ __launch_bounds__(kThreads) void k_mlp_gemm_nn(
     pb.init(P2 + (size_t)s0 * ldp, ldp, rows - s0, K, wave, lane, wb);
     gemm_mainloop_pp<T>(acc, pa, pb, smem, 0, K, wa);
   }
-  store_rows_bf16<T>(acc, out, ldo, rows, N, s0, n0, wa, wb, lane);
+  store_rows_bf16<T>(acc, out, ldo, rows, N, s0, n0, wa, wb, wave, lane, smem);
 }
 
 // ---------------------------------------------------------------------------
