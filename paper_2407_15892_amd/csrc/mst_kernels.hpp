@@ -443,47 +443,82 @@ __device__ __forceinline__ void dh_tile(
   int k_end = k_begin + ksteps_per_split * kBK;
   if (k_end > V) k_end = V;
 
+  // fp32 view of this tile's rows in the partial / running-sum array: a buffer descriptor over the valid rows
+  // (scalar base, 32-bit offsets, rows past the end dropped by the range check), columns masked per lane.
+  // Register r of accumulator tile (t, u) is row wa * 128 + 16 t + 4 (lane / 16) + r, column wb * 64 + 16 u + lane % 16.
+  const int rows_valid = rows - s0 < kTile ? rows - s0 : kTile;
+  float* const part = mode == kDhSplit ? partial + (size_t)sp * rows_stride * d : partial;
+  const __amdgpu_buffer_rsrc_t sums = make_rsrc_uniform(part + (size_t)s0 * d, (uint32_t)rows_valid * (uint32_t)d * 4u);
+  uint32_t lane_off[kTB16];
+  bool col_ok[kTB16];
+#pragma unroll
+  for (int u = 0; u < kTB16; ++u) {
+    const int j = j0 + wb * 64 + 16 * u + (lane & 15);
+    col_ok[u] = j < d;
+    lane_off[u] = ((uint32_t)(wa * 128 + 4 * (lane >> 4)) * (uint32_t)d + (uint32_t)j) * 4u;
+  }
+  auto row_off = [&](int t, int r) { return (uint32_t)(16 * t + r) * (uint32_t)d * 4u; };
+
   f32x4 acc[kTA16][kTB16];
   zero_acc<kTA16, kTB16>(acc);
+  if (mode == kDhAdd || mode == kDhLast) {
+    // the running sums of the earlier windows go straight into the accumulators (the loads fly while the first
+    // operand panels arrive) and are tied off so that the compiler puts no wait for them into the main loop
+#pragma unroll
+    for (int u = 0; u < kTB16; ++u)
+      if (col_ok[u]) {
+#pragma unroll
+        for (int t = 0; t < kTA16; ++t)
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            acc[t][u][r] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(sums, lane_off[u] + row_off(t, r), 0, 0));
+      }
+#pragma unroll
+    for (int t = 0; t < kTA16; ++t)
+#pragma unroll
+      for (int u = 0; u < kTB16; ++u) asm volatile("" : "+v"(acc[t][u]));
+  }
   PanelKC16<Tile16, kTile, kTA16, false> pa;
   PanelKS16<Tile16, kTile, kTB16> pb;
   pa.init(G + (size_t)s0 * ldg, ldg, rows - s0, ldg, wave, lane, wa);
   pb.init(W + j0, d, V, d - j0, wave, lane, wb);
   gemm_mainloop_pp<Tile16>(acc, pa, pb, smem, k_begin, k_end, wa);
 
-  if (mode == kDhAdd || mode == kDhLast) {
-    // running sums of the earlier windows: all loads first (the fragment registers are free now), then the adds
-#pragma unroll
-    for (int t = 0; t < kTA16; ++t)
-#pragma unroll
-      for (int u = 0; u < kTB16; ++u) {
-        const int j = j0 + wb * 64 + 16 * u + (lane & 15);
-        f32x4 old = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int s_local = s0 + wa * 128 + a_index_in_block16<false>(t, r, lane);
-          if (s_local < rows && j < d) old[r] = __builtin_nontemporal_load(partial + (size_t)s_local * d + j);
-        }
-        acc[t][u] += old;
-      }
-  }
   const bool to_bf16 = mode == kDhLast || (mode == kDhSplit && n_split == 1);
-  const float gamma = to_bf16 ? gamma_of(n_valid, grad_loss) : 1.0f;
-  float* part = mode == kDhSplit ? partial + (size_t)sp * rows_stride * d : partial;
+  if (!to_bf16) {
+#pragma unroll
+    for (int u = 0; u < kTB16; ++u)
+      if (col_ok[u]) {
+#pragma unroll
+        for (int t = 0; t < kTA16; ++t)
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[t][u][r]), sums, lane_off[u] + row_off(t, r), 0, 0);
+      }
+    return;
+  }
+  // bf16 result: the lanes of a wave instruction hold 16 adjacent columns of 4 rows, 32 bytes per row; staged in
+  // LDS (free after the main loop; rows padded to 528 bytes) the tile leaves as whole 512-byte rows
+  const float gamma = gamma_of(n_valid, grad_loss);
+  constexpr int kStageRow = kTile * 2 + 16;
 #pragma unroll
   for (int t = 0; t < kTA16; ++t)
 #pragma unroll
-    for (int u = 0; u < kTB16; ++u) {
-      const int j = j0 + wb * 64 + 16 * u + (lane & 15);
+    for (int u = 0; u < kTB16; ++u)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int s_local = s0 + wa * 128 + a_index_in_block16<false>(t, r, lane);
-        if (s_local < rows && j < d) {
-          if (to_bf16) dHc[(size_t)s_local * d + j] = (__bf16)(gamma * acc[t][u][r]);
-          else part[(size_t)s_local * d + j] = acc[t][u][r];
-        }
-      }
-    }
+      for (int r = 0; r < 4; ++r)
+        *reinterpret_cast<__bf16*>(smem + (wa * 128 + 16 * t + 4 * (lane >> 4) + r) * kStageRow +
+                                   (wb * 64 + 16 * u + (lane & 15)) * 2) = (__bf16)(gamma * acc[t][u][r]);
+  __syncthreads();
+  const int col = (lane & 31) * 8;                   // 8 columns = 16 bytes per lane, 32 lanes per row
+  const bool out_ok = j0 + col < d;                  // d % 8 == 0
+#pragma unroll
+  for (int i = 0; i < kTile / (2 * Tile16::kWaves); ++i) {
+    const int row = (kTile / Tile16::kWaves) * wave + 2 * i + (lane >> 5);
+    if (s0 + row < rows && out_ok)
+      *reinterpret_cast<bf16x8*>(dHc + (size_t)(s0 + row) * d + j0 + col) =
+          *reinterpret_cast<const bf16x8*>(smem + row * kStageRow + col * 2);
+  }
 }
 
 __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dh(
