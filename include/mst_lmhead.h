@@ -37,7 +37,10 @@
  *     keeps no state between calls (profiling events and the backward-schedule
  *     override of mst_set_bwd_schedule aside).
  *   - All work is enqueued on `stream` (a hipStream_t passed as void*); the
- *     calls return without waiting for the GPU.
+ *     calls return without waiting for the GPU.  They only launch kernels (no
+ *     allocation, no memset, no synchronisation), so after one eager call in the
+ *     process (which sets kernel attributes) they can be captured into a HIP
+ *     graph and replayed; profiling must be off while capturing.
  *   - Return value: MST_OK (0) or a negative error code.  Argument errors are
  *     found on the host before anything is launched.  A label outside [0, V)
  *     that is not `ignore_index` is a data error found on the device: it never

@@ -341,3 +341,48 @@ def test_block_schedule_does_not_overrun_the_workspace(schedule):
     run.backward()
     tail = run.last_ws[-4096:]
     assert bool((tail == 0xA5).all())
+
+
+def test_forward_and_backward_replay_from_a_hip_graph(schedule):
+    """The calls allocate nothing, never synchronise and only enqueue kernels, so a caller can capture them into a
+    HIP graph.  Every replay (with eager work and synchronisation in between) must reproduce the eager results bit for
+    bit, for both orders of the backward pass."""
+    import torch
+    import paper_2407_15892_amd as mst
+    from tests.gpu_harness import to_device_bf16
+    inp = mi.make_inputs(mi.custom_config(1024, 256, 6000, 4, index=431, w_std=0.3, ignore_frac=0.05))
+    S, d, V, M = 1024, 256, 6000, 4
+    H, W = to_device_bf16(inp.H_bits), to_device_bf16(inp.W_bits)
+    labels = torch.from_numpy(inp.labels).cuda()
+    fwd_bytes, bwd_bytes = mst.mst_workspace_bytes(S, d, V, M)
+    ws = torch.empty(max(fwd_bytes, bwd_bytes), dtype=torch.uint8, device="cuda")
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    lse = torch.empty(S, dtype=torch.float32, device="cuda")
+    nv = torch.zeros(1, dtype=torch.int64, device="cuda")
+    dH = torch.empty((S, d), dtype=torch.bfloat16, device="cuda")
+    dW = torch.empty((V, d), dtype=torch.float32, device="cuda")
+
+    def step():
+        mst.mst_lmhead_ce_fwd(H, W, labels, inp.ignore_index, M, ws, loss, lse, nv)
+        mst.mst_lmhead_ce_bwd(H, W, labels, inp.ignore_index, M, 1.0, lse, nv, ws, dH, dW)
+
+    for which in (mst.BWD_SCHEDULE_PAIRS, mst.BWD_SCHEDULE_BLOCKS_FUSED):
+        schedule(which)
+        step()                                   # eager reference (also the first call's one-time kernel attributes)
+        torch.cuda.synchronize()
+        ref = (loss.clone(), lse.clone(), dH.clone(), dW.clone())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        for _ in range(3):
+            loss.fill_(float("nan")); lse.fill_(float("nan")); dW.fill_(float("nan"))
+            dH.view(torch.int16).fill_(0x7FC0)
+            ws.fill_(0xA5)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(loss.view(torch.int32), ref[0].view(torch.int32))
+            assert torch.equal(lse.view(torch.int32), ref[1].view(torch.int32))
+            assert torch.equal(dH.view(torch.int16), ref[2].view(torch.int16))
+            assert torch.equal(dW.view(torch.int32), ref[3].view(torch.int32))
+        del graph
