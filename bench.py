@@ -34,9 +34,9 @@ GEMM_KINDS = {"fwd_gemm_lse": 2.0, "bwd_gemm_dlogits": 2.0, "bwd_gemm_dh": 2.0, 
 # (config, backward schedule, kernel kind).  The forward does not depend on the schedule.
 PMC_TRAFFIC_BYTES = {
     (2, "blocks", "fwd_gemm_lse"): 1.690e9 + 0.004e9,
-    (2, "blocks", "bwd_gemm_dlogits"): 1.659e9 + 0.266e9,
-    (2, "blocks", "bwd_gemm_dh"): 1.757e9 + 0.137e9,
-    (2, "blocks", "bwd_gemm_dw"): 1.631e9 + 0.284e9,
+    (2, "blocks", "bwd_gemm_dlogits"): 1.651e9 + 0.263e9,
+    (2, "blocks", "bwd_gemm_dh"): 1.716e9 + 0.146e9,
+    (2, "blocks", "bwd_gemm_dw"): 1.632e9 + 0.283e9,
     (2, "pairs", "fwd_gemm_lse"): 1.690e9 + 0.004e9,
     (2, "pairs", "bwd_gemm_dlogits"): 1.760e9 + 0.264e9,
     (2, "pairs", "bwd_gemm_dh"): 1.581e9 + 0.068e9,
@@ -92,11 +92,11 @@ MLP_FLOP_UNITS = {"gateup": 4.0, "down": 2.0, "da": 2.0, "gateup_bwd": 4.0, "dx"
 # HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of `bench.py --path mlp` (see profiles/)
 MLP_PMC_TRAFFIC_BYTES = {
     (2, "gateup"): 1.409e9 + 0.117e9,
-    (2, "down"): 0.705e9 + 0.036e9,
-    (2, "da"): 0.786e9 + 0.137e9,
+    (2, "down"): 0.705e9 + 0.034e9,
+    (2, "da"): 0.786e9 + 0.132e9,
     (2, "gateup_bwd"): 1.527e9 + 0.353e9,
-    (2, "dx"): 1.414e9 + 0.040e9,
-    (2, "dw"): 3.475e9 + 0.776e9,
+    (2, "dx"): 1.414e9 + 0.038e9,
+    (2, "dw"): 3.489e9 + 0.781e9,
 }
 
 
