@@ -122,30 +122,6 @@ struct PanelKC {
 #pragma unroll
     for (int kk = 0; kk < C::kKK; ++kk) rd[kk] = row0 * RB + (((2 * kk + (lane >> 5)) ^ swz(row0)) * 16);
   }
-  // Variant for a panel whose 32-row MFMA tiles come from different matrices: every wave loads exactly one
-  // 32-row tile of the panel (SPW * RPS == 32), `tile_base` points at the first of this wave's 32 source
-  // rows and `rows_valid` (may be <= 0) says how many of them exist.  Reading is as in init().
-  __device__ __forceinline__ void init_tile32(const void* tile_base, uint32_t ld_elems, int rows_valid, uint32_t k_elems,
-                                              int wave, int lane, int wave_side_index) {
-    static_assert(SPW * RPS == 32, "one 32-row tile per wave");
-    const uint32_t ld_bytes = ld_elems * 2;
-    const uint32_t rows = rows_valid <= 0 ? 0u : (rows_valid < 32 ? (uint32_t)rows_valid : 32u);
-    rsrc = make_rsrc_uniform(tile_base, rows * ld_bytes);
-    k_limit = k_elems;
-    slot0 = wave * SPW;
-    const int rin = lane / CPR, p = lane % CPR;
-#pragma unroll
-    for (int i = 0; i < SPW; ++i) {
-      const uint32_t lrow = RPS * (slot0 + i) + rin;
-      const uint32_t grow = a_row_of_mfma_row<kPermute>(lrow & 31);
-      const int chunk = p ^ swz(lrow);
-      kelem[i] = chunk * 8;
-      voff[i] = grow * ld_bytes + chunk * 16;
-    }
-    const int row0 = wave_side_index * (32 * TILES) + (lane & 31);
-#pragma unroll
-    for (int kk = 0; kk < C::kKK; ++kk) rd[kk] = row0 * RB + (((2 * kk + (lane >> 5)) ^ swz(row0)) * 16);
-  }
   __device__ __forceinline__ void issue(uint32_t panel_lds, uint32_t k0) const {
 #pragma unroll
     for (int i = 0; i < SPW; ++i)

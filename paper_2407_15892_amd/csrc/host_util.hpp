@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -12,9 +13,24 @@ namespace mst_host {
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) != 0; }
 
+// Runs a set-up step once per HIP device and remembers whether it worked: kernel attributes such as the
+// dynamic LDS limit belong to the device a kernel's code object is loaded on, not to the process.
+struct PerDeviceOnce {
+  static constexpr int kMaxDevices = 64;
+  std::mutex mu;
+  signed char state[kMaxDevices] = {};   // 0 = not run yet, 1 = done, -1 = failed
+  template <class F>
+  bool run(int dev, F step) {
+    if (dev < 0 || dev >= kMaxDevices) return step();   // beyond the table: repeat the step on every call
+    std::lock_guard<std::mutex> lk(mu);
+    if (state[dev] == 0) state[dev] = step() ? 1 : -1;
+    return state[dev] > 0;
+  }
+};
+
 struct Profiler {
   std::mutex mu;
-  bool enabled = false;
+  std::atomic<bool> enabled{false};
   struct Rec { int kind; hipEvent_t a, b; };
   std::vector<Rec> recs;
   std::vector<hipEvent_t> pool;
@@ -25,8 +41,7 @@ struct Profiler {
     return e;
   }
   void enable(bool on) {
-    std::lock_guard<std::mutex> lk(mu);
-    enabled = on;
+    enabled.store(on);
   }
   // adds elapsed ms / launch counts per kind, clears the record; false if an event could not be read
   bool collect(int n_kinds, double* ms_per_kind, int64_t* launches_per_kind) {
@@ -49,7 +64,7 @@ struct Profiler {
 
 struct Scope {   // brackets one launch with events when profiling is on
   Profiler& pr; hipStream_t st; int kind; hipEvent_t a = nullptr, b = nullptr; bool on;
-  Scope(Profiler& p, hipStream_t s, int k) : pr(p), st(s), kind(k), on(p.enabled) {
+  Scope(Profiler& p, hipStream_t s, int k) : pr(p), st(s), kind(k), on(p.enabled.load()) {
     if (!on) return;
     std::lock_guard<std::mutex> lk(pr.mu);
     a = pr.get(); b = pr.get();
@@ -60,6 +75,10 @@ struct Scope {   // brackets one launch with events when profiling is on
     if (b) (void)hipEventRecord(b, st);
     std::lock_guard<std::mutex> lk(pr.mu);
     if (a && b) pr.recs.push_back({kind, a, b});
+    else {   // an event could not be created: this launch goes unrecorded
+      if (a) pr.pool.push_back(a);
+      if (b) pr.pool.push_back(b);
+    }
   }
 };
 

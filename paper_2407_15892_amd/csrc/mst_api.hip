@@ -77,6 +77,7 @@ double rounds_us(int64_t tiles, int64_t k) {
 void choose_schedule(Plan* p) {
   const int64_t S = p->S, d = p->d, V = p->V, C = p->C;
   const int n_vt = p->n_vt, n_jt = p->n_jt;
+  const int forced = g_bwd_schedule.load();   // read once: another thread may change the override meanwhile
   // pairs
   double pairs = 0.0;
   for (int ia = 0; ia < p->n_chunks; ia += 2) {
@@ -133,9 +134,8 @@ void choose_schedule(Plan* p) {
     // fill whole rounds anyway (config 2: 512 and 1008 tiles), -1.5 to -2 % of the step where they do not (Gemma
     // shape: 896 dH tiles = 3.5 rounds; config 5: 496).  It is used when the two separate launches would leave at
     // least kFuseWaste of their CU time idle; the block shapes are ranked without it.
-    const int forced_now = g_bwd_schedule.load();
-    const bool fuse = forced_now == MST_BWD_SCHEDULE_BLOCKS_FUSED ||
-                      (forced_now == MST_BWD_SCHEDULE_AUTO && sep_us - work_us >= kFuseWaste * sep_us);
+    const bool fuse = forced == MST_BWD_SCHEDULE_BLOCKS_FUSED ||
+                      (forced == MST_BWD_SCHEDULE_AUTO && sep_us - work_us >= kFuseWaste * sep_us);
     const double t_pick = t;
     if (!p->blk_use || t_pick < best) {
       best = t_pick;
@@ -147,7 +147,6 @@ void choose_schedule(Plan* p) {
     }
   }
   p->est_blocks_us = best;
-  const int forced = g_bwd_schedule.load();
   if (forced == MST_BWD_SCHEDULE_PAIRS) p->blk_use = false;
   else if (forced == MST_BWD_SCHEDULE_AUTO && p->blk_use && !(best < pairs)) p->blk_use = false;
   // MST_BWD_SCHEDULE_BLOCKS and _BLOCKS_FUSED keep the best block shape whenever one fits
@@ -218,12 +217,11 @@ struct Scope : mst_host::Scope {
   Scope(hipStream_t s, int k) : mst_host::Scope(g_prof, s, k) {}
 };
 
-std::once_flag g_attr_once;
-hipError_t g_attr_err = hipSuccess;
-void set_kernel_attributes() {
-  auto set = [](const void* f) {
-    hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (e != hipSuccess && g_attr_err == hipSuccess) g_attr_err = e;
+mst_host::PerDeviceOnce g_attr_once;
+bool set_kernel_attributes() {   // on the current device
+  bool ok = true;
+  auto set = [&ok](const void* f) {
+    if (hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess) ok = false;
   };
   set((const void*)k_fwd_gemm_lse);
   set((const void*)k_bwd_gemm_dlogits);
@@ -232,6 +230,7 @@ void set_kernel_attributes() {
   set((const void*)k_bwd_gemm_dw<true>);
   set((const void*)k_bwd_gemm_dh_dw<false>);
   set((const void*)k_bwd_gemm_dh_dw<true>);
+  return ok;
 }
 
 mst_status check_launch() { return hipGetLastError() == hipSuccess ? MST_OK : MST_ERR_LAUNCH; }
@@ -239,8 +238,10 @@ mst_status check_launch() { return hipGetLastError() == hipSuccess ? MST_OK : MS
 mst_status prepare_device() {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return MST_ERR_NO_DEVICE;
-  std::call_once(g_attr_once, set_kernel_attributes);
-  if (g_attr_err != hipSuccess) return MST_ERR_LAUNCH;
+  if (!g_attr_once.run(dev, set_kernel_attributes)) {
+    (void)hipGetLastError();
+    return MST_ERR_LAUNCH;
+  }
   return MST_OK;
 }
 

@@ -45,12 +45,11 @@ struct Scope : mst_host::Scope {
   Scope(hipStream_t s, int k) : mst_host::Scope(g_prof, s, k) {}
 };
 
-std::once_flag g_attr_once;
-hipError_t g_attr_err = hipSuccess;
-void set_kernel_attributes() {
-  auto set = [](const void* f) {
-    hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (e != hipSuccess && g_attr_err == hipSuccess) g_attr_err = e;
+mst_host::PerDeviceOnce g_attr_once;
+bool set_kernel_attributes() {   // on the current device
+  bool ok = true;
+  auto set = [&ok](const void* f) {
+    if (hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess) ok = false;
   };
   set((const void*)k_mlp_gateup<false>);
   set((const void*)k_mlp_gateup<true>);
@@ -59,6 +58,7 @@ void set_kernel_attributes() {
   set((const void*)k_mlp_gemm_nn<Tile16HalfB>);
   set((const void*)k_mlp_dw3<false>);
   set((const void*)k_mlp_dw3<true>);
+  return ok;
 }
 
 mst_status check_launch() { return hipGetLastError() == hipSuccess ? MST_OK : MST_ERR_LAUNCH; }
@@ -66,8 +66,10 @@ mst_status check_launch() { return hipGetLastError() == hipSuccess ? MST_OK : MS
 mst_status prepare_device() {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return MST_ERR_NO_DEVICE;
-  std::call_once(g_attr_once, set_kernel_attributes);
-  if (g_attr_err != hipSuccess) return MST_ERR_LAUNCH;
+  if (!g_attr_once.run(dev, set_kernel_attributes)) {
+    (void)hipGetLastError();
+    return MST_ERR_LAUNCH;
+  }
   return MST_OK;
 }
 
