@@ -206,6 +206,18 @@ def test_many_row_tiles_per_chunk():
     _check_full(mi.make_inputs(cfg))
 
 
+@pytest.mark.parametrize("S,d,V,M", [
+    (600, 136, 23000, 1),     # 3 x 90 tiles per chunk: several tiles per workgroup, ragged rows, K and vocabulary
+    (1300, 128, 14000, 1),    # 6 x 55 tiles, shortest K the multi-tile forward accepts
+    (257, 264, 66000, 1),     # 2 x 258 tiles: the second row tile holds one row
+])
+def test_more_tiles_than_compute_units(S, d, V, M):
+    """More than 256 tiles per launch: forward workgroups walk over several tiles with the operand pipeline
+    running across tile boundaries; labels land in every part of a tile."""
+    cfg = mi.custom_config(S, d, V, M, index=330 + M + d, w_std=0.3, ignore_frac=0.05, label_dist="zipf")
+    _check_full(mi.make_inputs(cfg), grad_loss=0.5)
+
+
 def test_repeated_calls_reuse_the_same_buffers():
     """Back-to-back calls on one stream with the same workspace (as bench.py does) stay correct."""
     import torch
