@@ -122,10 +122,12 @@ struct PanelKC {
 #pragma unroll
     for (int kk = 0; kk < C::kKK; ++kk) rd[kk] = row0 * RB + (((2 * kk + (lane >> 5)) ^ swz(row0)) * 16);
   }
+  __device__ __forceinline__ void issue_one(int i, uint32_t panel_lds, uint32_t k0) const {
+    dma16(rsrc, (k0 + kelem[i]) < k_limit ? voff[i] + k0 * 2 : kOutOfRange, panel_lds + (slot0 + i) * 1024);
+  }
   __device__ __forceinline__ void issue(uint32_t panel_lds, uint32_t k0) const {
 #pragma unroll
-    for (int i = 0; i < SPW; ++i)
-      dma16(rsrc, (k0 + kelem[i]) < k_limit ? voff[i] + k0 * 2 : kOutOfRange, panel_lds + (slot0 + i) * 1024);
+    for (int i = 0; i < SPW; ++i) issue_one(i, panel_lds, k0);
   }
   __device__ __forceinline__ bf16x8 frag(const char* panel, int t, int kk) const {
     return *reinterpret_cast<const bf16x8*>(panel + rd[kk] + t * (32 * RB));
@@ -178,10 +180,12 @@ struct PanelKS {
       rd[t] = krow * RB + (((col >> 3) ^ (kSwz * (i16 >> 2))) * 16) + (col & 7) * 2;
     }
   }
+  __device__ __forceinline__ void issue_one(int i, uint32_t panel_lds, uint32_t k0) const {
+    dma16(rsrc, ((ok_mask >> i) & 1u) ? voff[i] + k0 * ld_bytes : kOutOfRange, panel_lds + (slot0 + i) * 1024);
+  }
   __device__ __forceinline__ void issue(uint32_t panel_lds, uint32_t k0) const {
 #pragma unroll
-    for (int i = 0; i < SPW; ++i)
-      dma16(rsrc, ((ok_mask >> i) & 1u) ? voff[i] + k0 * ld_bytes : kOutOfRange, panel_lds + (slot0 + i) * 1024);
+    for (int i = 0; i < SPW; ++i) issue_one(i, panel_lds, k0);
   }
   __device__ __forceinline__ bf16x8 frag(const char* panel, int t, int kk) const {
     typedef __attribute__((address_space(3))) i16x4* lds_i16x4_ptr;
@@ -222,21 +226,29 @@ __device__ __forceinline__ void gemm_mainloop_pp(typename C::Acc (&acc)[C::TA][C
   int ca = 0, cb = 0;                          // stage indices of step kt
   for (int kt = 0; kt < nk; ++kt) {
     // ---- memory phase
-    {
-      int na = ca + C::NSA - 1; if (na >= C::NSA) na -= C::NSA;
-      const int nb = cb ^ 1;
-      pb.issue(ldsB + nb * C::kPanelB, k_begin + (kt + 1) * C::BK);
-      pa.issue(ldsA + na * C::kPanelA, k_begin + (kt + 2) * C::BK);
-    }
+    int na = ca + C::NSA - 1; if (na >= C::NSA) na -= C::NSA;
+    const int nb = cb ^ 1;
     const char* a_panel = smem + ca * C::kPanelA;
     const char* b_panel = smemB + cb * C::kPanelB;
     bf16x8 a[C::kKK][C::TA], b[C::kKK][C::TB];
+    {
+      // Each global->LDS load is followed by its share of the fragment reads: a wave's vector-memory instruction
+      // waits for the CU's one address unit (16 clocks per 1 KB load, and the four waves of this half issue 32 of
+      // them per phase), and LDS reads queued behind it would wait too.  Interleaved, both units work at once:
+      // the memory phase, which was the longer of the two (1120 against 1086 clocks), drops below the compute
+      // phase.  The A loads stay last: the wait that opens the next step counts on them being the newest.
+      constexpr int kLoads = PB::SPW + PA::SPW, kFrags = C::kKK * (C::TA + C::TB);
 #pragma unroll
-    for (int kk = 0; kk < C::kKK; ++kk) {
+      for (int j = 0; j < kLoads; ++j) {
+        if (j < PB::SPW) pb.issue_one(j, ldsB + nb * C::kPanelB, k_begin + (kt + 1) * C::BK);
+        else pa.issue_one(j - PB::SPW, ldsA + na * C::kPanelA, k_begin + (kt + 2) * C::BK);
 #pragma unroll
-      for (int t = 0; t < C::TA; ++t) a[kk][t] = pa.frag(a_panel, t, kk);
-#pragma unroll
-      for (int u = 0; u < C::TB; ++u) b[kk][u] = pb.frag(b_panel, u, kk);
+        for (int f = j * kFrags / kLoads; f < (j + 1) * kFrags / kLoads; ++f) {
+          const int kk = f / (C::TA + C::TB), r = f % (C::TA + C::TB);
+          if (r < C::TA) a[kk][r] = pa.frag(a_panel, r, kk);
+          else b[kk][r - C::TA] = pb.frag(b_panel, r - C::TA, kk);
+        }
+      }
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     if (group == 1) wait_vmcnt<kAhead>();      // group 1 reaches the barrier that opens step kt + 1 right after this phase

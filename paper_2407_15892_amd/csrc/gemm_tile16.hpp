@@ -94,10 +94,12 @@ struct PanelKC16 {
     init_map(base, ld_elems, rows, k_elems, wave, lane, wave_side_index,
              [](int lrow) { return (lrow & ~127) + a_row_of_block_row16<kPermute>(lrow & 127); }, true);
   }
+  __device__ __forceinline__ void issue_one(int i, uint32_t panel_lds, uint32_t k0) const {
+    dma16(rsrc, (k0 + kelem[i]) < k_limit ? voff[i] + k0 * 2 : kOutOfRange, panel_lds + (slot0 + i) * 1024);
+  }
   __device__ __forceinline__ void issue(uint32_t panel_lds, uint32_t k0) const {
 #pragma unroll
-    for (int i = 0; i < SPW; ++i)
-      dma16(rsrc, (k0 + kelem[i]) < k_limit ? voff[i] + k0 * 2 : kOutOfRange, panel_lds + (slot0 + i) * 1024);
+    for (int i = 0; i < SPW; ++i) issue_one(i, panel_lds, k0);
   }
   __device__ __forceinline__ bf16x8 frag(const char* panel, int t, int kk) const {
     return *reinterpret_cast<const bf16x8*>(panel + rd[kk] + t * (16 * RB));
@@ -156,10 +158,12 @@ struct PanelKS16 {
       rd[t] = krow * RB + (((col >> 3) ^ swz(krow)) * 16) + (col & 7) * 2;
     }
   }
+  __device__ __forceinline__ void issue_one(int i, uint32_t panel_lds, uint32_t k0) const {
+    dma16(rsrc, ((ok_mask >> i) & 1u) ? voff[i] + k0 * ld_bytes : kOutOfRange, panel_lds + (slot0 + i) * 1024);
+  }
   __device__ __forceinline__ void issue(uint32_t panel_lds, uint32_t k0) const {
 #pragma unroll
-    for (int i = 0; i < SPW; ++i)
-      dma16(rsrc, ((ok_mask >> i) & 1u) ? voff[i] + k0 * ld_bytes : kOutOfRange, panel_lds + (slot0 + i) * 1024);
+    for (int i = 0; i < SPW; ++i) issue_one(i, panel_lds, k0);
   }
   __device__ __forceinline__ bf16x8 frag(const char* panel, int t, int kk) const {
     typedef __attribute__((address_space(3))) i16x4* lds_i16x4_ptr;
