@@ -75,64 +75,6 @@ template <bool kPermute> __device__ __forceinline__ int a_row_of_mfma_row(int i)
   if (!kPermute) return i;
   return 16 * ((i >> 2) & 1) + 4 * (i >> 3) + (i & 3);
 }
-template <bool kPermute> __device__ __forceinline__ int a_index_in_tile(int r, int lane) {
-  if (kPermute) return 16 * (lane >> 5) + r;
-  return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-}
-
-// K-contiguous panel [EXT rows][BK k]; LDS row = MFMA row order (a permutation, if any, is applied at the source)
-template <class C, int EXT, int TILES, bool kPermute>
-struct PanelKC {
-  static constexpr int BK = C::BK;
-  static constexpr int RB = BK * 2;             // bytes per LDS row
-  static constexpr int CPR = BK / 8;            // 16-byte chunks per row
-  static constexpr int RPS = 1024 / RB;         // rows per 1 KiB slot
-  static constexpr int NSLOT = EXT / RPS;
-  static constexpr int SPW = NSLOT / C::kWaves; // slots per wave
-  static_assert(NSLOT % C::kWaves == 0, "slots must divide over waves");
-  static constexpr int kBytes = EXT * RB;
-  __amdgpu_buffer_rsrc_t rsrc;
-  uint32_t voff[SPW];
-  uint32_t kelem[SPW];
-  uint32_t k_limit, slot0;
-  uint32_t rd[C::kKK];
-
-  // XOR swizzle of the 16-byte chunk index.  ds_read_b128 serves 16 lanes (256 bytes, all 64 banks)
-  // per clock; the 16 lanes of a quarter wave read 16 consecutive rows at one logical chunk, so
-  // the chunk index is XORed with the row bits that do not already select a bank.
-  __device__ __forceinline__ static int swz(int row) { return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
-
-  __device__ __forceinline__ void init(const void* base, uint32_t ld_elems, uint32_t rows_valid, uint32_t k_elems,
-                                       int wave, int lane, int wave_side_index) {
-    const uint32_t ld_bytes = ld_elems * 2;
-    const uint32_t rows = rows_valid < (uint32_t)EXT ? rows_valid : (uint32_t)EXT;
-    rsrc = make_rsrc(base, rows * ld_bytes);
-    k_limit = k_elems;
-    slot0 = wave * SPW;
-    const int rin = lane / CPR, p = lane % CPR;
-#pragma unroll
-    for (int i = 0; i < SPW; ++i) {
-      const uint32_t lrow = RPS * (slot0 + i) + rin;                                   // LDS row
-      const uint32_t grow = (lrow & ~31u) + a_row_of_mfma_row<kPermute>(lrow & 31);    // global row
-      const int chunk = p ^ swz(lrow);
-      kelem[i] = chunk * 8;
-      voff[i] = grow * ld_bytes + chunk * 16;
-    }
-    const int row0 = wave_side_index * (32 * TILES) + (lane & 31);
-#pragma unroll
-    for (int kk = 0; kk < C::kKK; ++kk) rd[kk] = row0 * RB + (((2 * kk + (lane >> 5)) ^ swz(row0)) * 16);
-  }
-  __device__ __forceinline__ void issue_one(int i, uint32_t panel_lds, uint32_t k0) const {
-    dma16(rsrc, (k0 + kelem[i]) < k_limit ? voff[i] + k0 * 2 : kOutOfRange, panel_lds + (slot0 + i) * 1024);
-  }
-  __device__ __forceinline__ void issue(uint32_t panel_lds, uint32_t k0) const {
-#pragma unroll
-    for (int i = 0; i < SPW; ++i) issue_one(i, panel_lds, k0);
-  }
-  __device__ __forceinline__ bf16x8 frag(const char* panel, int t, int kk) const {
-    return *reinterpret_cast<const bf16x8*>(panel + rd[kk] + t * (32 * RB));
-  }
-};
 
 // K-strided panel [BK k][EXT index].  kPermute (A side only): MFMA row m of a 32-wide tile reads index
 // a_row_of_mfma_row(m), so that a lane's 16 accumulator registers hold 16 consecutive indices.  The

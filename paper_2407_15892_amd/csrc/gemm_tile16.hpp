@@ -40,12 +40,6 @@ template <bool kPermute> __device__ __forceinline__ int a_row_of_block_row16(int
   if (!kPermute) return m;
   return 32 * ((m >> 2) & 3) + 4 * (m >> 4) + (m & 3);
 }
-// A index (within the wave's 128-row block) of accumulator register r of tile t in a lane
-template <bool kPermute> __device__ __forceinline__ int a_index_in_block16(int t, int r, int lane) {
-  const int g = lane >> 4;
-  return kPermute ? 32 * g + 4 * t + r : 16 * t + 4 * g + r;
-}
-
 // K-contiguous panel [EXT rows][BK k]; LDS row = MFMA row order (a permutation, if any, is applied at the source)
 template <class C, int EXT, int TILES, bool kPermute>
 struct PanelKC16 {
@@ -64,7 +58,9 @@ struct PanelKC16 {
   uint32_t k_limit, slot0;
   uint32_t rd[C::kKK];
 
-  // as in PanelKC: 16 lanes read 16 consecutive rows at one logical 16-byte chunk per clock
+  // XOR swizzle of the 16-byte chunk index.  ds_read_b128 serves 16 lanes (256 bytes, all 64 banks) per clock;
+  // the 16 lanes of a quarter wave read 16 consecutive rows at one logical chunk, so the chunk index is XORed
+  // with the row bits that do not already select a bank.
   __device__ __forceinline__ static int swz(int row) { return (row >> 1) & 7; }
 
   // `row_of(lrow)`: source row, relative to `base`, that LDS row lrow of the panel holds; rows >= rows_valid read zeros
