@@ -127,7 +127,7 @@ def main_mlp(args) -> int:
     import torch
     import mst_inputs as mi
     import paper_2407_15892_amd as mst
-    from tests.gpu_harness import to_device_bf16
+    from mst_inputs import to_device_bf16
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
@@ -245,7 +245,7 @@ def main() -> int:
     import torch
     import mst_inputs as mi
     import paper_2407_15892_amd as mst
-    from tests.gpu_harness import to_device_bf16
+    from mst_inputs import to_device_bf16
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)

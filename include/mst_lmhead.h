@@ -34,8 +34,8 @@
  * Conventions
  *   - Every pointer named below is a DEVICE pointer owned by the caller, except
  *     where "host" is written.  The library allocates no device memory and
- *     keeps no state between calls (profiling events and the backward-schedule
- *     override of mst_set_bwd_schedule aside).
+ *     keeps no state between calls (profiling events and the calling thread's
+ *     backward-schedule override of mst_set_bwd_schedule aside).
  *   - All work is enqueued on `stream` (a hipStream_t passed as void*); the
  *     calls return without waiting for the GPU.  They only launch kernels (no
  *     allocation, no memset, no synchronisation), so after one eager call in the
@@ -45,7 +45,11 @@
  *     found on the host before anything is launched.  A label outside [0, V)
  *     that is not `ignore_index` is a data error found on the device: it never
  *     causes an out-of-range access; the forward call then writes NaN to *loss
- *     and -1 to *n_valid.
+ *     and -1 to *n_valid, and the backward call (given that -1, or counting the
+ *     labels itself) fills dH and dW with NaN.
+ *   - The device must be a whole MI355X (256 compute units behind one HIP
+ *     device); a partitioned device is refused with MST_ERR_NO_DEVICE because the
+ *     tile maps are laid out for 8 XCDs of 32 compute units.
  *   - Requirements: d % 8 == 0; H, W, dH 16-byte aligned; dW, lse 4-byte
  *     aligned; workspace 256-byte aligned; 1 <= M <= S; d < 2^22;
  *     V * d < 2^31; ceil(S/M) * (V rounded up to 8) < 2^30.
@@ -78,7 +82,7 @@ enum {
   MST_ERR_WORKSPACE = -4,      /* workspace NULL or smaller than required          */
   MST_ERR_ALIGNMENT = -5,      /* a pointer is not aligned as required             */
   MST_ERR_LAUNCH = -6,         /* the HIP runtime refused a launch                 */
-  MST_ERR_NO_DEVICE = -7       /* no gfx950 device is current                      */
+  MST_ERR_NO_DEVICE = -7       /* no current device, or not a whole 256-CU gfx950  */
 };
 
 /* Human-readable text for a status code (host; static storage). */
@@ -159,7 +163,9 @@ mst_status mst_lmhead_ce_fwd(const void* H, const void* W, const int32_t* labels
  *   grad_loss  upstream d(objective)/d(loss) (the algorithm's "nabla loss"), host value
  *   lse        optional fp32 [S] from the forward call (NULL: recomputed here)
  *   n_valid    optional int64 scalar from the forward call on the same labels and
- *              ignore_index (NULL: recounted here); it is trusted, not re-checked
+ *              ignore_index (NULL: recounted here, range check included); a supplied
+ *              value is trusted, not re-checked; a negative one (the forward's report
+ *              of a label outside [0, V)) makes dH and dW NaN
  *   dH         out, bf16 [S, d], fully overwritten (ignored rows are exactly 0)
  *   dW         out, fp32 [V, d], fully overwritten
  */
@@ -186,14 +192,18 @@ mst_status mst_lmhead_ce_bwd(const void* H, const void* W, const int32_t* labels
  *                            workgroups instead of leaving one each (same arithmetic as BLOCKS, bit for bit).
  *   MST_BWD_SCHEDULE_AUTO    (default) whichever a host-side cost model (rounds of workgroups plus fp32
  *                            gradient traffic) ranks faster for the shape.
- * mst_set_bwd_schedule: host, process-wide, takes effect at the next call; MST_ERR_BAD_SHAPE for an unknown
- * value.  mst_bwd_schedule_info: host, pure; fills info[0..7] = {schedule that would run, rows per block,
- * row blocks, vocabulary entries per window, windows, dH split count, cost estimate of PAIRS in us, of
- * the block order that would be chosen in us (0 if no block shape fits)}.
+ * mst_set_bwd_schedule: host; the override belongs to the CALLING THREAD (thread-local, AUTO in every new
+ * thread) and takes effect at that thread's next backward call, so one caller's setting never changes the
+ * summation order of another thread's call; MST_ERR_BAD_SHAPE for an unknown value.
+ * mst_bwd_schedule_info_for: host, pure (no hidden state); fills info[0..7] = {schedule that would run
+ * under the override `schedule`, rows per block, row blocks, vocabulary entries per window, windows, dH
+ * split count, cost estimate of PAIRS in us, of the block order that would be chosen in us (0 if no block
+ * shape fits)}.  mst_bwd_schedule_info: the same with the calling thread's current override.
  */
 enum { MST_BWD_SCHEDULE_AUTO = 0, MST_BWD_SCHEDULE_PAIRS = 1, MST_BWD_SCHEDULE_BLOCKS = 2, MST_BWD_SCHEDULE_BLOCKS_FUSED = 3 };
 mst_status mst_set_bwd_schedule(int32_t schedule);
 mst_status mst_bwd_schedule_info(int64_t S, int64_t d, int64_t V, int32_t M, int64_t* info);
+mst_status mst_bwd_schedule_info_for(int64_t S, int64_t d, int64_t V, int32_t M, int32_t schedule, int64_t* info);
 
 /*
  * Matrix-core probe (measurement aid, not part of the path).  Enqueues a kernel in

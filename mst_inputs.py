@@ -54,6 +54,18 @@ def bf16_bits_to_f64(b: np.ndarray) -> np.ndarray:
     return bf16_bits_to_f32(b).astype(np.float64)
 
 
+def to_device_bf16(bits: np.ndarray):
+    """bfloat16 bit patterns -> a torch bf16 tensor on the current GPU (a copy of the bits, no arithmetic)."""
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def bf16_tensor_to_f64(t) -> np.ndarray:
+    """A torch bf16 tensor (any device) -> float64 numpy array, exact."""
+    import torch
+    return bf16_bits_to_f64(t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16))
+
+
 # ----------------------------------------------------------------------------
 # configurations
 # ----------------------------------------------------------------------------

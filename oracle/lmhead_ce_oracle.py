@@ -142,7 +142,7 @@ def lmhead_ce_grads_sampled(H, W, labels, lse, n_valid, rows, vocab_rows,
     W = np.asarray(W, dtype=np.float64)
     labels = np.asarray(labels)
     S = H.shape[0]
-    valid = labels != ignore_index
+    valid = _check_labels(labels, W.shape[0], ignore_index)
     scale = grad_loss / n_valid if n_valid > 0 else 0.0
     rows = np.asarray(rows, dtype=np.int64)
     vocab_rows = np.asarray(vocab_rows, dtype=np.int64)

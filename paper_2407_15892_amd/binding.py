@@ -69,6 +69,9 @@ def load_library() -> ctypes.CDLL:
     lib.mst_set_bwd_schedule.argtypes = [c.c_int32]
     lib.mst_bwd_schedule_info.restype = c.c_int
     lib.mst_bwd_schedule_info.argtypes = [c.c_int64, c.c_int64, c.c_int64, c.c_int32, c.POINTER(c.c_int64)]
+    lib.mst_bwd_schedule_info_for.restype = c.c_int
+    lib.mst_bwd_schedule_info_for.argtypes = [c.c_int64, c.c_int64, c.c_int64, c.c_int32, c.c_int32,
+                                              c.POINTER(c.c_int64)]
     lib.mst_profile_enable.restype = c.c_int
     lib.mst_profile_enable.argtypes = [c.c_int]
     lib.mst_profile_collect.restype = c.c_int
@@ -164,9 +167,14 @@ def mst_set_bwd_schedule(schedule: int) -> None:
     _check(load_library().mst_set_bwd_schedule(int(schedule)))
 
 
-def mst_bwd_schedule_info(S: int, d: int, V: int, M: int) -> dict:
+def mst_bwd_schedule_info(S: int, d: int, V: int, M: int, schedule: Optional[int] = None) -> dict:
+    """What the backward call would run: under the calling thread's override, or (schedule given) under that
+    override without touching any state."""
     info = (ctypes.c_int64 * 8)()
-    _check(load_library().mst_bwd_schedule_info(S, d, V, M, info))
+    if schedule is None:
+        _check(load_library().mst_bwd_schedule_info(S, d, V, M, info))
+    else:
+        _check(load_library().mst_bwd_schedule_info_for(S, d, V, M, int(schedule), info))
     keys = ("schedule", "rows_per_block", "row_blocks", "vocab_per_window", "windows", "dh_split",
             "est_pairs_us", "est_blocks_us")
     return dict(zip(keys, (int(x) for x in info)))

@@ -19,7 +19,9 @@ constexpr int kNumCu = 256;          // MI355X compute units; only steers the sc
 constexpr int kMaxDhSplit = 16;
 constexpr int kMaxWindows = 64;      // most vocabulary windows the block schedule considers
 
-std::atomic<int> g_bwd_schedule{MST_BWD_SCHEDULE_AUTO};
+// Override of the backward order, per calling thread: a caller that forces an order cannot change the
+// summation order of a call another thread is making at the same time.
+thread_local int t_bwd_schedule = MST_BWD_SCHEDULE_AUTO;
 
 using mst_host::align_up;
 using mst_host::misaligned;
@@ -74,10 +76,9 @@ double rounds_us(int64_t tiles, int64_t k) {
   return (double)((tiles + kNumCu - 1) / kNumCu) * (double)((k + kBK - 1) / kBK) * kUsPerKStep;
 }
 
-void choose_schedule(Plan* p) {
+void choose_schedule(Plan* p, int forced) {
   const int64_t S = p->S, d = p->d, V = p->V, C = p->C;
   const int n_vt = p->n_vt, n_jt = p->n_jt;
-  const int forced = g_bwd_schedule.load();   // read once: another thread may change the override meanwhile
   // pairs
   double pairs = 0.0;
   for (int ia = 0; ia < p->n_chunks; ia += 2) {
@@ -152,7 +153,8 @@ void choose_schedule(Plan* p) {
   // MST_BWD_SCHEDULE_BLOCKS and _BLOCKS_FUSED keep the best block shape whenever one fits
 }
 
-mst_status make_plan(int64_t S, int64_t d, int64_t V, int32_t M, Plan* p) {
+// `forced`: one of the MST_BWD_SCHEDULE_* values; only the backward's block shape depends on it
+mst_status make_plan(int64_t S, int64_t d, int64_t V, int32_t M, Plan* p, int forced = MST_BWD_SCHEDULE_AUTO) {
   if (S <= 0 || d <= 0 || V <= 0) return MST_ERR_BAD_SHAPE;
   if (d % 8 != 0) return MST_ERR_BAD_SHAPE;
   if (M < 1 || (int64_t)M > S) return MST_ERR_BAD_M;
@@ -207,7 +209,7 @@ mst_status make_plan(int64_t S, int64_t d, int64_t V, int32_t M, Plan* p) {
   p->b_lse = p->b_ctl + sizeof(Control);
   p->b_fwd = p->b_lse + align_up((size_t)S * 4, 256);
   p->b_total_max = p->b_fwd + p->f_total;
-  choose_schedule(p);
+  choose_schedule(p, forced);
   return MST_OK;
 }
 
@@ -217,7 +219,14 @@ struct Scope : mst_host::Scope {
   Scope(hipStream_t s, int k) : mst_host::Scope(g_prof, s, k) {}
 };
 
-mst_host::PerDeviceOnce g_attr_once;
+mst_host::PerDeviceOnce g_attr_once, g_shape_once;
+// The tile maps and the schedule's cost model are written for the whole chip: kNumCu compute units in kNumXcd
+// XCDs.  A partitioned device (fewer compute units behind one HIP device) would be mis-tiled, so it is refused.
+bool device_is_whole_chip(int dev) {
+  int cus = 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return false;
+  return cus == kNumCu;
+}
 bool set_kernel_attributes() {   // on the current device
   bool ok = true;
   auto set = [&ok](const void* f) {
@@ -238,6 +247,10 @@ mst_status check_launch() { return hipGetLastError() == hipSuccess ? MST_OK : MS
 mst_status prepare_device() {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return MST_ERR_NO_DEVICE;
+  if (!g_shape_once.run(dev, [dev] { return device_is_whole_chip(dev); })) {
+    (void)hipGetLastError();
+    return MST_ERR_NO_DEVICE;
+  }
   if (!g_attr_once.run(dev, set_kernel_attributes)) {
     (void)hipGetLastError();
     return MST_ERR_LAUNCH;
@@ -284,7 +297,7 @@ const char* mst_strerror(mst_status s) {
     case MST_ERR_WORKSPACE: return "workspace is NULL or too small (see mst_workspace_bytes)";
     case MST_ERR_ALIGNMENT: return "pointer alignment: H, W, dH 16 bytes; workspace 256 bytes; lse, dW 4 bytes";
     case MST_ERR_LAUNCH: return "the HIP runtime refused a kernel launch or attribute";
-    case MST_ERR_NO_DEVICE: return "no current HIP device";
+    case MST_ERR_NO_DEVICE: return "no current HIP device, or it is not a whole 256-CU gfx950 chip";
     default: return "unknown status";
   }
 }
@@ -369,7 +382,7 @@ mst_status mst_lmhead_ce_bwd(const void* H, const void* W, const int32_t* labels
                              const int64_t* n_valid, void* workspace, size_t workspace_bytes,
                              void* dH, float* dW, void* stream) {
   Plan p;
-  mst_status s = make_plan(S, d, V, M, &p);
+  mst_status s = make_plan(S, d, V, M, &p, t_bwd_schedule);
   if (s != MST_OK) return s;
   if (!H || !W || !labels || !dH || !dW) return MST_ERR_NULL_POINTER;
   const size_t need = !lse ? p.b_total_max : (!n_valid ? p.b_lse : p.b_total);
@@ -387,7 +400,7 @@ mst_status mst_lmhead_ce_bwd(const void* H, const void* W, const int32_t* labels
     Control* ctl = reinterpret_cast<Control*>(ws + p.b_ctl);
     Scope sc(st, MST_K_LABEL_SCAN);
     hipLaunchKernelGGL(k_label_scan, dim3(1), dim3(1024), 0, st, labels, (long long)S, (int)V, ignore_index, ctl);
-    nv = &ctl->n_valid;
+    nv = &ctl->n_valid_checked;   // -1 if a label is outside [0, V): dH and dW then come out NaN
   }
   if (!lse) {
     // no saved log-sum-exp: run the forward's pass first, in the tail of the workspace
@@ -506,14 +519,19 @@ mst_status mst_lmhead_ce_bwd(const void* H, const void* W, const int32_t* labels
 
 mst_status mst_set_bwd_schedule(int32_t schedule) {
   if (schedule < MST_BWD_SCHEDULE_AUTO || schedule > MST_BWD_SCHEDULE_BLOCKS_FUSED) return MST_ERR_BAD_SHAPE;
-  g_bwd_schedule.store(schedule);
+  t_bwd_schedule = schedule;
   return MST_OK;
 }
 
 mst_status mst_bwd_schedule_info(int64_t S, int64_t d, int64_t V, int32_t M, int64_t* info) {
+  return mst_bwd_schedule_info_for(S, d, V, M, t_bwd_schedule, info);
+}
+
+mst_status mst_bwd_schedule_info_for(int64_t S, int64_t d, int64_t V, int32_t M, int32_t schedule, int64_t* info) {
   if (!info) return MST_ERR_NULL_POINTER;
+  if (schedule < MST_BWD_SCHEDULE_AUTO || schedule > MST_BWD_SCHEDULE_BLOCKS_FUSED) return MST_ERR_BAD_SHAPE;
   Plan p;
-  const mst_status s = make_plan(S, d, V, M, &p);
+  const mst_status s = make_plan(S, d, V, M, &p, schedule);
   if (s != MST_OK) return s;
   info[0] = p.blk_use ? (p.blk_fused ? MST_BWD_SCHEDULE_BLOCKS_FUSED : MST_BWD_SCHEDULE_BLOCKS) : MST_BWD_SCHEDULE_PAIRS;
   info[1] = p.blk_use ? p.blk_rows : 2 * (int64_t)p.C;

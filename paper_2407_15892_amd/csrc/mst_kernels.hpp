@@ -47,15 +47,20 @@ constexpr int kNumXcd = 8;
 struct Control {
   long long n_valid;    // rows whose label is neither ignored nor out of range
   int bad_labels;       // rows whose label is outside [0, V) and not the ignore value
-  int pad[61];
+  int pad0;
+  long long n_valid_checked;   // n_valid, or -1 if bad_labels > 0: what a caller (or the backward pass) is handed
+  int pad[58];
 };
 static_assert(sizeof(Control) == 256, "control block is one 256-byte line");
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// gamma = grad_loss / N_valid (Algorithm 4 lines 9-10 and the mean of the loss), 0 when nothing is valid
+// gamma = grad_loss / N_valid (Algorithm 4 lines 9-10 and the mean of the loss), 0 when nothing is valid.
+// A negative count is the forward's (or the label scan's) report of a label outside [0, V): the gradients
+// are then NaN throughout, like the loss.
 __device__ __forceinline__ float gamma_of(const long long* __restrict__ n_valid, float grad_loss) {
   const long long nv = *n_valid;
+  if (nv < 0) return __builtin_nanf("");
   return nv > 0 ? (float)((double)grad_loss / (double)nv) : 0.f;
 }
 
@@ -122,6 +127,7 @@ __global__ __launch_bounds__(1024) void k_label_scan(const int* __restrict__ lab
     for (int i = 0; i < 16; ++i) { tv += s_valid[i]; tb += s_bad[i]; }
     ctl->n_valid = tv;
     ctl->bad_labels = tb;
+    ctl->n_valid_checked = tb > 0 ? -1 : tv;
   }
 }
 

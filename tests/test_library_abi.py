@@ -212,3 +212,35 @@ def test_profile_kind_count_matches_the_library(mst):
     header = open(os.path.join(os.path.dirname(__file__), "..", "include", "mst_lmhead.h")).read()
     enum = header[header.index("MST_K_LABEL_SCAN = 0"):header.index("MST_PROFILE_KINDS\n")]
     assert enum.count("MST_K_") == len(names)
+
+
+def test_schedule_override_is_per_thread_and_the_pure_query_ignores_it(mst):
+    """The override set by one thread is invisible to another thread's calls, and mst_bwd_schedule_info_for answers
+    for an explicit override without reading or changing any state."""
+    import threading
+    shape = (8192, 4096, 128256, 8)
+    seen = {}
+    try:
+        mst.mst_set_bwd_schedule(mst.BWD_SCHEDULE_PAIRS)
+        assert mst.mst_bwd_schedule_info(*shape)["schedule"] == mst.BWD_SCHEDULE_PAIRS
+
+        def other():
+            seen["fresh_thread"] = mst.mst_bwd_schedule_info(*shape)["schedule"]
+            mst.mst_set_bwd_schedule(mst.BWD_SCHEDULE_BLOCKS_FUSED)
+            seen["after_own_set"] = mst.mst_bwd_schedule_info(*shape)["schedule"]
+
+        th = threading.Thread(target=other)
+        th.start()
+        th.join()
+        assert seen["fresh_thread"] == mst.BWD_SCHEDULE_BLOCKS          # AUTO's choice for this shape
+        assert seen["after_own_set"] == mst.BWD_SCHEDULE_BLOCKS_FUSED
+        assert mst.mst_bwd_schedule_info(*shape)["schedule"] == mst.BWD_SCHEDULE_PAIRS   # this thread's is untouched
+        for forced, want in ((mst.BWD_SCHEDULE_AUTO, mst.BWD_SCHEDULE_BLOCKS), (mst.BWD_SCHEDULE_PAIRS, mst.BWD_SCHEDULE_PAIRS),
+                             (mst.BWD_SCHEDULE_BLOCKS_FUSED, mst.BWD_SCHEDULE_BLOCKS_FUSED)):
+            assert mst.mst_bwd_schedule_info(*shape, schedule=forced)["schedule"] == want
+        assert mst.mst_bwd_schedule_info(*shape)["schedule"] == mst.BWD_SCHEDULE_PAIRS
+        info = (ctypes.c_int64 * 8)()
+        assert mst.load_library().mst_bwd_schedule_info_for(*shape, 9, info) == -2
+        assert mst.load_library().mst_bwd_schedule_info_for(*shape, 0, None) == -1
+    finally:
+        mst.mst_set_bwd_schedule(mst.BWD_SCHEDULE_AUTO)

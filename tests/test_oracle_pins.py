@@ -360,3 +360,13 @@ def test_shift_labels_matches_the_sliced_next_token_loss():
     assert (orc.shift_labels(np.arange(4, dtype=np.int32), 4, 1) == -100).all()
     with pytest.raises(ValueError):
         orc.shift_labels(tok, B, L + 1)
+
+
+def test_sampled_gradients_reject_out_of_range_labels_like_the_full_oracle():
+    rng = np.random.default_rng(5)
+    H, W = rng.standard_normal((6, 4)), rng.standard_normal((5, 4))
+    y = np.array([0, 1, 7, -100, 2, 4])       # 7 is outside [0, 5)
+    with pytest.raises(ValueError):
+        orc.lmhead_ce(H, W, y)
+    with pytest.raises(ValueError):
+        orc.lmhead_ce_grads_sampled(H, W, y, np.zeros(6), 5, [0], [0])
