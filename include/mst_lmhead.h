@@ -159,6 +159,35 @@ mst_status mst_lmhead_ce_fwd(const void* H, const void* W, const int32_t* labels
                              void* stream);
 
 /*
+ * The forward call for callers that cannot allocate device memory or pass a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, outputs and arithmetic as mst_lmhead_ce_fwd
+ * (loss, lse and n_valid are bit-identical to its results), but the scratch
+ * memory is a static device array inside the library, MST_STATIC_SCRATCH_BYTES
+ * (32 MiB) per GPU the library runs on, held until the process ends.  The call
+ * allocates nothing (no hipMalloc / hipFree, no allocating library routine) and
+ * only enqueues kernels on `stream`.
+ *   - Limit: the (max, sum-exp) pairs of ONE mini-sequence plus 4 bytes per row of
+ *     the call must fit, ceil(S/M) * (8 * ceil(V/256) + 4) + 4 * S + 1024 <=
+ *     MST_STATIC_SCRATCH_BYTES; otherwise MST_ERR_WORKSPACE and nothing is
+ *     launched (raise M, or use mst_lmhead_ce_fwd with a workspace).  Within the
+ *     limit the pairs of as many consecutive mini-sequences as fit are merged by
+ *     one launch; at S = 32768, V = 128256, M = 32 that is 8 of the 32.
+ *   - Every call on a GPU uses that GPU's one array, which keeps the previous
+ *     call's contents; nothing in it has to start at zero (every word a kernel
+ *     reads has been written earlier in the same call).  Calls that overlap on
+ *     one GPU (two streams, two threads) race on it: serialise them.
+ *   - Other errors as for mst_lmhead_ce_fwd; MST_ERR_LAUNCH also if the array's
+ *     device address cannot be obtained.
+ */
+#define MST_STATIC_SCRATCH_BYTES (32 * 1024 * 1024)
+mst_status mst_lmhead_ce_fwd_static(const void* H, const void* W, const int32_t* labels,
+                                    int64_t S, int64_t d, int64_t V,
+                                    int32_t ignore_index, int32_t M,
+                                    float* loss, float* lse, int64_t* n_valid,
+                                    void* stream);
+
+/*
  * Backward: mini-sequence LM-head gradients with recomputation (Algorithm 4).
  *   grad_loss  upstream d(objective)/d(loss) (the algorithm's "nabla loss"), host value
  *   lse        optional fp32 [S] from the forward call (NULL: recomputed here)

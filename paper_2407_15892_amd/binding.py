@@ -61,6 +61,9 @@ def load_library() -> ctypes.CDLL:
     lib.mst_lmhead_ce_fwd.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int64, c.c_int64,
                                       c.c_int32, c.c_int32, c.c_void_p, c.c_size_t,
                                       c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
+    lib.mst_lmhead_ce_fwd_static.restype = c.c_int
+    lib.mst_lmhead_ce_fwd_static.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int64, c.c_int64,
+                                             c.c_int32, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
     lib.mst_lmhead_ce_bwd.restype = c.c_int
     lib.mst_lmhead_ce_bwd.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int64, c.c_int64,
                                       c.c_int32, c.c_int32, c.c_float, c.c_void_p, c.c_void_p,
@@ -145,6 +148,19 @@ def mst_lmhead_ce_fwd(H, W, labels, ignore_index: int, M: int, workspace, loss, 
     _check(load_library().mst_lmhead_ce_fwd(
         _ptr(H), _ptr(W), _ptr(labels), S, d, V, ignore_index, M,
         _ptr(workspace), workspace.numel() * workspace.element_size(),
+        _ptr(loss), _ptr(lse), _ptr(n_valid), _stream_handle(stream)))
+
+
+STATIC_SCRATCH_BYTES = 32 * 1024 * 1024     # MST_STATIC_SCRATCH_BYTES of include/mst_lmhead.h
+
+
+def mst_lmhead_ce_fwd_static(H, W, labels, ignore_index: int, M: int, loss, lse=None, n_valid=None,
+                             stream=None) -> None:
+    """Enqueue the forward pass on the library's static device scratch (no workspace argument, no allocation)."""
+    S, d = H.shape
+    V = W.shape[0]
+    _check(load_library().mst_lmhead_ce_fwd_static(
+        _ptr(H), _ptr(W), _ptr(labels), S, d, V, ignore_index, M,
         _ptr(loss), _ptr(lse), _ptr(n_valid), _stream_handle(stream)))
 
 

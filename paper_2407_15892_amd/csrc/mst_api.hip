@@ -153,8 +153,11 @@ void choose_schedule(Plan* p, int forced) {
   // MST_BWD_SCHEDULE_BLOCKS and _BLOCKS_FUSED keep the best block shape whenever one fits
 }
 
-// `forced`: one of the MST_BWD_SCHEDULE_* values; only the backward's block shape depends on it
-mst_status make_plan(int64_t S, int64_t d, int64_t V, int32_t M, Plan* p, int forced = MST_BWD_SCHEDULE_AUTO) {
+// `forced`: one of the MST_BWD_SCHEDULE_* values; only the backward's block shape depends on it.
+// `fwd_cap`: if non-zero, the forward's groups of mini-sequences are shortened until the forward workspace fits
+// into that many bytes (one mini-sequence per group at least; the caller checks f_total against the cap).
+mst_status make_plan(int64_t S, int64_t d, int64_t V, int32_t M, Plan* p, int forced = MST_BWD_SCHEDULE_AUTO,
+                     size_t fwd_cap = 0) {
   if (S <= 0 || d <= 0 || V <= 0) return MST_ERR_BAD_SHAPE;
   if (d % 8 != 0) return MST_ERR_BAD_SHAPE;
   if (M < 1 || (int64_t)M > S) return MST_ERR_BAD_M;
@@ -193,6 +196,11 @@ mst_status make_plan(int64_t S, int64_t d, int64_t V, int32_t M, Plan* p, int fo
   {
     const int64_t per_chunk = ((int64_t)p->n_vt * 8 + 4) * C;
     int64_t g = (C * ldg * 2) / per_chunk;
+    if (fwd_cap) {
+      const int64_t fixed = (int64_t)sizeof(Control) + (S * 4 + 255) / 256 * 256 + 512;   // control, nll, padding
+      const int64_t by_cap = ((int64_t)fwd_cap - fixed) / per_chunk;
+      if (g > by_cap) g = by_cap;
+    }
     if (g < 1) g = 1;
     if (g > p->n_chunks) g = p->n_chunks;
     p->fwd_group_rows = g * C;
@@ -284,6 +292,56 @@ mst_status run_forward_chunks(const Plan& p, const __bf16* H, const __bf16* W, c
   return check_launch();
 }
 
+mst_status check_forward_alignment(const void* H, const void* W, const int32_t* labels, const float* loss,
+                                   const float* lse, const int64_t* n_valid) {
+  if (misaligned(H, 16) || misaligned(W, 16) || misaligned(lse, 4) || misaligned(labels, 4) || misaligned(loss, 4) ||
+      misaligned(n_valid, 8))
+    return MST_ERR_ALIGNMENT;
+  return MST_OK;
+}
+
+// label scan, the chunk loop, the loss: everything the forward call enqueues, on workspace `ws` of p.f_total bytes
+mst_status enqueue_forward(const Plan& p, const void* H, const void* W, const int32_t* labels, int32_t ignore_index,
+                           char* ws, float* loss, float* lse, int64_t* n_valid, void* stream) {
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  Control* ctl = reinterpret_cast<Control*>(ws);
+  float* nll = reinterpret_cast<float*>(ws + p.f_nll);
+  {
+    Scope sc(st, MST_K_LABEL_SCAN);
+    hipLaunchKernelGGL(k_label_scan, dim3(1), dim3(1024), 0, st, labels, (long long)p.S, (int)p.V, ignore_index, ctl);
+  }
+  const mst_status s = run_forward_chunks(p, static_cast<const __bf16*>(H), static_cast<const __bf16*>(W), labels,
+                                          ignore_index, ws, lse, nll, st);
+  if (s != MST_OK) return s;
+  {
+    Scope sc(st, MST_K_LOSS_REDUCE);
+    hipLaunchKernelGGL(k_loss_reduce, dim3(1), dim3(1024), 0, st, nll, (long long)p.S, ctl, loss,
+                       reinterpret_cast<long long*>(n_valid));
+  }
+  return check_launch();
+}
+
+// Scratch of the entry point that allocates nothing: one array per GPU, part of the code object, alive until
+// the process ends.  Its name is only a host-side handle; the device address is asked for once per device
+// (with that device current) and kept, and only that address is ever handed to a kernel.
+__device__ __align__(256) static unsigned char scratch[MST_STATIC_SCRATCH_BYTES];
+std::mutex g_scratch_mu;
+char* g_scratch_ptr[mst_host::PerDeviceOnce::kMaxDevices] = {};
+char* static_scratch_of_current_device() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= mst_host::PerDeviceOnce::kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = static_cast<char*>(ptr);
+  }
+  return g_scratch_ptr[dev];
+}
+
 }  // namespace
 
 extern "C" {
@@ -354,27 +412,25 @@ mst_status mst_lmhead_ce_fwd(const void* H, const void* W, const int32_t* labels
   if (s != MST_OK) return s;
   if (!H || !W || !labels || !loss) return MST_ERR_NULL_POINTER;
   if (!workspace || workspace_bytes < p.f_total) return MST_ERR_WORKSPACE;
-  if (misaligned(H, 16) || misaligned(W, 16) || misaligned(workspace, 256) || misaligned(lse, 4) ||
-      misaligned(labels, 4) || misaligned(loss, 4) || misaligned(n_valid, 8))
-    return MST_ERR_ALIGNMENT;
+  if (misaligned(workspace, 256)) return MST_ERR_ALIGNMENT;
+  if ((s = check_forward_alignment(H, W, labels, loss, lse, n_valid)) != MST_OK) return s;
   if ((s = prepare_device()) != MST_OK) return s;
-  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-  char* ws = static_cast<char*>(workspace);
-  Control* ctl = reinterpret_cast<Control*>(ws);
-  float* nll = reinterpret_cast<float*>(ws + p.f_nll);
-  {
-    Scope sc(st, MST_K_LABEL_SCAN);
-    hipLaunchKernelGGL(k_label_scan, dim3(1), dim3(1024), 0, st, labels, (long long)S, (int)V, ignore_index, ctl);
-  }
-  s = run_forward_chunks(p, static_cast<const __bf16*>(H), static_cast<const __bf16*>(W), labels, ignore_index,
-                         ws, lse, nll, st);
+  return enqueue_forward(p, H, W, labels, ignore_index, static_cast<char*>(workspace), loss, lse, n_valid, stream);
+}
+
+mst_status mst_lmhead_ce_fwd_static(const void* H, const void* W, const int32_t* labels, int64_t S, int64_t d, int64_t V,
+                                    int32_t ignore_index, int32_t M, float* loss, float* lse, int64_t* n_valid,
+                                    void* stream) {
+  Plan p;
+  mst_status s = make_plan(S, d, V, M, &p, MST_BWD_SCHEDULE_AUTO, (size_t)MST_STATIC_SCRATCH_BYTES);
   if (s != MST_OK) return s;
-  {
-    Scope sc(st, MST_K_LOSS_REDUCE);
-    hipLaunchKernelGGL(k_loss_reduce, dim3(1), dim3(1024), 0, st, nll, (long long)S, ctl, loss,
-                       reinterpret_cast<long long*>(n_valid));
-  }
-  return check_launch();
+  if (!H || !W || !labels || !loss) return MST_ERR_NULL_POINTER;
+  if (p.f_total > (size_t)MST_STATIC_SCRATCH_BYTES) return MST_ERR_WORKSPACE;   // one mini-sequence alone is too large
+  if ((s = check_forward_alignment(H, W, labels, loss, lse, n_valid)) != MST_OK) return s;
+  if ((s = prepare_device()) != MST_OK) return s;
+  char* ws = static_scratch_of_current_device();
+  if (!ws) return MST_ERR_LAUNCH;
+  return enqueue_forward(p, H, W, labels, ignore_index, ws, loss, lse, n_valid, stream);
 }
 
 mst_status mst_lmhead_ce_bwd(const void* H, const void* W, const int32_t* labels, int64_t S, int64_t d, int64_t V,

@@ -244,3 +244,14 @@ def test_schedule_override_is_per_thread_and_the_pure_query_ignores_it(mst):
         assert mst.load_library().mst_bwd_schedule_info_for(*shape, 0, None) == -1
     finally:
         mst.mst_set_bwd_schedule(mst.BWD_SCHEDULE_AUTO)
+
+
+def test_static_scratch_forward_rejects_what_does_not_fit(mst):
+    """A call whose per-row scratch alone exceeds the static array: refused on the host, nothing launched."""
+    lib = mst.load_library()
+    S, d, V, M = 8_400_000, 8, 8, 8400     # 4 bytes per row = 33.6 MB > 32 MiB
+    assert 4 * S > mst.binding.STATIC_SCRATCH_BYTES
+    fake = 0x10000
+    assert mst.binding.mst_workspace_bytes_status(S, d, V, M) == 0          # the shape itself is accepted
+    rc = lib.mst_lmhead_ce_fwd_static(fake, fake, fake, S, d, V, -100, M, fake, None, None, None)
+    assert rc == -4 and "workspace" in mst.mst_strerror(rc)
