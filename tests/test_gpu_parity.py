@@ -314,6 +314,60 @@ def test_block_schedule_matches_oracle(schedule, S, d, V, M, blocks, windows, fu
     _check_full(mi.make_inputs(cfg), grad_loss=0.8, use_lse=False)
 
 
+@pytest.mark.parametrize("which", ["pairs_one_chunk", "blocks"])
+def test_dlogits_block_left_in_the_workspace_matches_oracle(schedule, which):
+    """The only direct look at the bf16 dlogits block (Algorithm 4 line 6): after a backward call the start of the
+    workspace still holds the block written last -- with one mini-sequence and the printed loop that is all rows x all
+    of V (leading dimension V rounded up to 8), with the block order the last row block x the last vocabulary window
+    (leading dimension = entries per window).  It is compared element by element with the oracle's UNSCALED
+    softmax - onehot: the kernel rounds to bf16 (8 significant bits, nearest even: half an ulp is between 2^-9 and
+    2^-8 of the value, for the label entry p - 1 too), and its fp32 logits and log-sum-exp add a relative 1e-4 at most."""
+    import torch
+    import paper_2407_15892_amd as mst
+    DeviceRun, bf2f = _harness()
+    if which == "pairs_one_chunk":
+        S, d, V, M = 700, 136, 3003, 1
+        schedule(mst.BWD_SCHEDULE_PAIRS)
+    else:
+        S, d, V, M = 1800, 136, 2900, 12
+        schedule(mst.BWD_SCHEDULE_BLOCKS)
+    info = mst.mst_bwd_schedule_info(S, d, V, M)
+    inp = mi.make_inputs(mi.custom_config(S, d, V, M, index=430, w_std=0.3, ignore_frac=0.1, label_dist="zipf"))
+    run = DeviceRun(inp, M=M)
+    run.forward()
+    run.backward(grad_loss=0.7)          # the block is unscaled: grad_loss must not show in it
+    if which == "pairs_one_chunk":
+        assert info["schedule"] == mst.BWD_SCHEDULE_PAIRS
+        r0, rows, v0, cols, ld = 0, S, 0, V, (V + 7) // 8 * 8
+    else:
+        assert info["schedule"] == mst.BWD_SCHEDULE_BLOCKS and info["windows"] >= 2 and info["row_blocks"] >= 2, info
+        R, Vw = info["rows_per_block"], info["vocab_per_window"]
+        r0 = (info["row_blocks"] - 1) * R
+        rows = S - r0
+        v0 = (info["windows"] - 1) * Vw
+        cols, ld = V - v0, Vw
+    G = bf2f(run.last_ws[: rows * ld * 2].view(torch.bfloat16).view(rows, ld))
+    H64, W64 = inp.H_f64(), inp.W_f64()
+    z = orc.logits_f64(H64[r0:r0 + rows], W64)
+    lse = orc.row_logsumexp(z)
+    y = inp.labels[r0:r0 + rows]
+    valid = y != inp.ignore_index
+    g_ref = orc.dlogits_rows(z, lse, y, valid, 1.0)[:, v0:v0 + cols]
+    err = np.abs(G[:, :cols] - g_ref)
+    bound = (2.0 ** -8 + 1e-4) * np.abs(g_ref) + 1e-30
+    worst = float((err / bound).max())
+    print(f"dlogits block {which}: {rows} x {cols}, worst error / bound = {worst:.3f}; "
+          f"label entries in block: {int((valid & (y >= v0) & (y < v0 + cols)).sum())}")
+    assert worst <= 1.0
+    assert np.all(G[~valid] == 0.0), "ignored rows must be exactly zero"
+    assert np.all(G[:, cols:ld if which == 'pairs_one_chunk' else min(ld, (cols + 255) // 256 * 256)] == 0.0), \
+        "padding columns must be zero"
+    in_block = valid & (y >= v0) & (y < v0 + cols)
+    assert in_block.sum() > 10
+    lab = G[np.flatnonzero(in_block), (y - v0)[in_block]]
+    assert np.all(lab < 0.0) and np.all(lab >= -1.0) and lab.mean() < -0.9, "label entries are p - 1"
+
+
 def test_block_and_pair_schedules_agree_and_repeat_bit_for_bit(schedule):
     DeviceRun, bf2f = _harness()
     import torch
