@@ -3,10 +3,18 @@
 
 One "step" is one forward call plus one backward call (with logit
 recomputation) over one batch of seeded synthetic input that is already
-resident in HBM.  The workload is the Llama3-8B-shaped configuration
-(S=8192, d=4096, V=128256, M=8).  Prints ONE JSON line.
+resident in HBM.  The workload is the long-sequence Llama3-8B-shaped
+configuration the target is stated on (config 3: S=32768, d=4096, V=128256,
+M=32).  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--no-cpu-baseline]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--no-cpu-baseline]
+
+`value` and `ms_per_step` come from the wall clock around the K timed steps (synchronised on both sides);
+`step_ms` gives median / min / max of the individual steps from events recorded between them on the same stream.
+The per-kernel figures (`kernels`, `roofline`) come from HIP events the library records around every launch on
+the caller's stream INSIDE that timed region (so `value` includes their small cost; `--no-kernel-timing` leaves
+them out).  `roofline.traffic` is read from profiles/pmc_traffic_per_launch.txt, the table the rocprofv3 counter
+summaries in profiles/ cite.
 
 `--path mlp` times the mini-sequence MLP block instead (forward + backward with recomputation of the
 intermediates, Llama3-8B shape S=8192, d=4096, I=14336, chunk size C = d) and prints the same kind of line.
@@ -29,19 +37,22 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 # executed flop per step of each GEMM kernel kind, in units of S*d*V (a kind with no launches in a run is skipped)
 GEMM_KINDS = {"fwd_gemm_lse": 2.0, "bwd_gemm_dlogits": 2.0, "bwd_gemm_dh": 2.0, "bwd_gemm_dw": 2.0, "bwd_gemm_dh_dw": 4.0}
 
-# Bytes fetched and written beyond L2 per launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command
-# (see profiles/), scaled by what the same counters read for a device copy of known size; keyed by
-# (config, backward schedule, kernel kind).  The forward does not depend on the schedule.
-PMC_TRAFFIC_BYTES = {
-    (2, "blocks", "fwd_gemm_lse"): 1.690e9 + 0.004e9,
-    (2, "blocks", "bwd_gemm_dlogits"): 1.651e9 + 0.263e9,
-    (2, "blocks", "bwd_gemm_dh"): 1.716e9 + 0.146e9,
-    (2, "blocks", "bwd_gemm_dw"): 1.632e9 + 0.283e9,
-    (2, "pairs", "fwd_gemm_lse"): 1.690e9 + 0.004e9,
-    (2, "pairs", "bwd_gemm_dlogits"): 1.760e9 + 0.264e9,
-    (2, "pairs", "bwd_gemm_dh"): 1.581e9 + 0.068e9,
-    (2, "pairs", "bwd_gemm_dw"): 4.855e9 + 2.101e9,
-}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "pmc_traffic_per_launch.txt")
+
+
+def pmc_traffic_bytes(path_name: str, config: int, schedule: str, kernel: str):
+    """Bytes fetched + written beyond L2 per launch of `kernel`, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+    this command scaled by a copy of known size: a line `path config schedule kernel fetched_bytes written_bytes` of
+    the table under profiles/ (schedule `-` = any).  None if the table has no such line."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            for line in f:
+                t = line.split("#")[0].split()
+                if len(t) == 6 and t[0] == path_name and int(t[1]) == config and t[2] in (schedule, "-") and t[3] == kernel:
+                    return float(t[4]) + float(t[5])
+    except OSError:
+        pass
+    return None
 
 
 def mfma_probe(mst, torch):
@@ -89,16 +100,6 @@ def cpu_baseline(inp, sample_rows: int):
 MLP_KINDS = ("gateup", "down", "da", "gateup_bwd", "dx", "dw")
 # executed flop per step of each MLP kernel kind, in units of S*d*I
 MLP_FLOP_UNITS = {"gateup": 4.0, "down": 2.0, "da": 2.0, "gateup_bwd": 4.0, "dx": 4.0, "dw": 6.0}
-# HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of `bench.py --path mlp` (see profiles/)
-MLP_PMC_TRAFFIC_BYTES = {
-    (2, "gateup"): 1.409e9 + 0.117e9,
-    (2, "down"): 0.705e9 + 0.034e9,
-    (2, "da"): 0.786e9 + 0.132e9,
-    (2, "gateup_bwd"): 1.527e9 + 0.353e9,
-    (2, "dx"): 1.414e9 + 0.038e9,
-    (2, "dw"): 3.489e9 + 0.781e9,
-}
-
 
 def mlp_cpu_baseline(inp, sample_rows: int):
     """The fp64 MLP oracle as it stands, timed on the host cores on the first `sample_rows` tokens."""
@@ -195,7 +196,7 @@ def main_mlp(args) -> int:
         achieved = fl / (ms / n * 1e-3) / 1e12
         roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                    "traffic": MLP_PMC_TRAFFIC_BYTES.get((args.config, dom)),
+                    "traffic": pmc_traffic_bytes("mlp", args.config, "-", dom),
                     "flop_per_launch": fl, "avg_launch_ms": ms / n, "launches_per_step": n / args.steps}
     out = {
         "metric": "MsT-MLP fwd+bwd TFLOP/s (22*S*d*I executed flop incl. recomputation)",
@@ -224,7 +225,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--config", type=int, default=None,
+                    help="workload: LM-head configs 1-5 (default 3, the target configuration), MLP configs 1-4 (default 2)")
     ap.add_argument("--cpu-sample-rows", type=int, default=4096)
     ap.add_argument("--bwd-schedule", choices=("auto", "pairs", "blocks", "blocks_fused"), default="auto",
                     help="order of the LM-head backward pass (default: the library's own choice)")
@@ -238,6 +240,8 @@ def main() -> int:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
               file=sys.stderr)
         return 2
+    if args.config is None:
+        args.config = 2 if args.path == "mlp" else 3
     if args.path == "mlp":
         return main_mlp(args)
 
@@ -302,14 +306,18 @@ def main() -> int:
 
     timing = not args.no_kernel_timing
     mst.mst_profile_enable(timing)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record(stream)
+    for i in range(args.steps):
         step()
+        marks[i + 1].record(stream)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     kern = mst.mst_profile_collect() if timing else {}
     mst.mst_profile_enable(False)
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
 
     ms_per_step = dt * 1e3 / args.steps
     f_exec = 8.0 * S * d * V                      # fwd GEMM + recompute + dH + dW
@@ -328,7 +336,7 @@ def main() -> int:
         dom = max(GEMM_KINDS, key=lambda k: kern.get(k, (0.0, 0))[0])
         ms, n = kern[dom]
         achieved = flop_per_launch(dom) / (ms / n * 1e-3) / 1e12
-        traffic = PMC_TRAFFIC_BYTES.get((args.config, sched["schedule"], dom))
+        traffic = pmc_traffic_bytes("lmhead", args.config, sched["schedule"], dom)
         roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
                     "flop_per_launch": flop_per_launch(dom), "avg_launch_ms": ms / n,
@@ -352,6 +360,14 @@ def main() -> int:
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
+        "step_ms": {"median": per_step[len(per_step) // 2] if len(per_step) % 2 else
+                    0.5 * (per_step[len(per_step) // 2 - 1] + per_step[len(per_step) // 2]),
+                    "min": per_step[0], "max": per_step[-1], "n": len(per_step),
+                    "what": "individual timed steps, events between steps on the launch stream"},
+        "kernel_timing": ("per-launch HIP events recorded by the library inside the timed region" if timing
+                          else "off"),
+        "target": {"frac_of_bf16_peak": 0.60, "ms_per_step_at_target": f_exec / (0.60 * PEAK_BF16_TFLOPS * 1e12) * 1e3,
+                   "gap_ms": ms_per_step - f_exec / (0.60 * PEAK_BF16_TFLOPS * 1e12) * 1e3},
         "config": {"workload": f"config {cfg.index} {cfg.name}: S={S} d={d} V={V} M={M} (C={cfg.C}), "
                                f"bf16 H/W, int32 labels, fwd+bwd with logit recomputation",
                    "S": S, "d": d, "V": V, "M": M},
