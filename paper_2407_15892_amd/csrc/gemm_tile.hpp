@@ -63,9 +63,14 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc_uniform(const void* 
   const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
   return make_rsrc(reinterpret_cast<const void*>(((uint64_t)hi << 32) | lo), __builtin_amdgcn_readfirstlane(bytes));
 }
+// m0 (the LDS base of the load) is written here without being declared: the compiler treats m0 as reserved and
+// rejects it in a clobber list ("may not be preserved across the asm statement ... undefined behaviour"), so a
+// declaration would promise nothing.  It never keeps a value of its own in m0 across statements on this target:
+// it loads m0 immediately in front of each of its own uses (LDS-DMA intrinsics, s_sendmsg, GWS, interpolation),
+// none of which these kernels contain.  A kernel that adds one must not interleave it with this function.
 __device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t rsrc, uint32_t voffset, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-               :: "s"(lds_addr), "v"(voffset), "s"(rsrc) : "memory", "m0");
+               :: "s"(lds_addr), "v"(voffset), "s"(rsrc) : "memory");
 }
 template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
 __device__ __forceinline__ uint32_t lds_addr_of(const void* p) {
