@@ -227,6 +227,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=None,
                     help="workload: LM-head configs 1-5 (default 3, the target configuration), MLP configs 1-4 (default 2)")
+    ap.add_argument("--m", type=int, default=None,
+                    help="LM-head path: override the number of mini-sequences M of the chosen configuration (sweeps)")
+    ap.add_argument("--rows", type=int, default=None,
+                    help="LM-head path: override the number of tokens S (same value distributions, own seed stream)")
     ap.add_argument("--cpu-sample-rows", type=int, default=4096)
     ap.add_argument("--bwd-schedule", choices=("auto", "pairs", "blocks", "blocks_fused"), default="auto",
                     help="order of the LM-head backward pass (default: the library's own choice)")
@@ -259,6 +263,11 @@ def main() -> int:
                               "blocks": mst.BWD_SCHEDULE_BLOCKS,
                               "blocks_fused": mst.BWD_SCHEDULE_BLOCKS_FUSED}[args.bwd_schedule])
     cfg = mi.CONFIGS[args.config]
+    if args.m is not None or args.rows is not None:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, S=args.rows or cfg.S, M=args.m or cfg.M,
+                                  name=cfg.name + "-variant" + (f"-S{args.rows}" if args.rows else "") +
+                                  (f"-M{args.m}" if args.m else ""))
     sched = mst.mst_bwd_schedule_info(cfg.S, cfg.d, cfg.V, cfg.M)
     sched["schedule"] = {mst.BWD_SCHEDULE_PAIRS: "pairs", mst.BWD_SCHEDULE_BLOCKS: "blocks",
                          mst.BWD_SCHEDULE_BLOCKS_FUSED: "blocks_fused"}[sched["schedule"]]
@@ -336,7 +345,7 @@ def main() -> int:
         dom = max(GEMM_KINDS, key=lambda k: kern.get(k, (0.0, 0))[0])
         ms, n = kern[dom]
         achieved = flop_per_launch(dom) / (ms / n * 1e-3) / 1e12
-        traffic = pmc_traffic_bytes("lmhead", args.config, sched["schedule"], dom)
+        traffic = None if (args.m or args.rows) else pmc_traffic_bytes("lmhead", args.config, sched["schedule"], dom)
         roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
                     "flop_per_launch": flop_per_launch(dom), "avg_launch_ms": ms / n,

@@ -235,6 +235,19 @@ mst_status mst_bwd_schedule_info(int64_t S, int64_t d, int64_t V, int32_t M, int
 mst_status mst_bwd_schedule_info_for(int64_t S, int64_t d, int64_t V, int32_t M, int32_t schedule, int64_t* info);
 
 /*
+ * Workgroup -> tile map of the GEMM kernels (host-only test aid; the kernels call the same function).  A launch
+ * over an n_slow x n_fast space of 256 x 256 tiles has mst_tile_grid(n_slow, n_fast) workgroups; workgroup b lands
+ * on XCD b % 8, which owns a contiguous range of the slow coordinate and walks it in 4 x 8 rectangles of tiles:
+ * order 0 (forward, dH, dW kernels) band by band of 4 slow tiles inside super-groups of 32 fast tiles, order 1
+ * (dlogits kernel) group by group of 8 fast tiles.  mst_tile_of_workgroup writes the tile of workgroup `workgroup`
+ * and returns 1, or returns 0 for a padding workgroup (it exits at once), or -1 for bad arguments.  Every tile is
+ * the image of exactly one workgroup.
+ */
+int32_t mst_tile_grid(int32_t n_slow, int32_t n_fast);
+int32_t mst_tile_of_workgroup(int32_t n_slow, int32_t n_fast, int32_t order, int32_t workgroup,
+                              int32_t* slow, int32_t* fast);
+
+/*
  * Matrix-core probe (measurement aid, not part of the path).  Enqueues a kernel in
  * which every wave of `blocks` workgroups of 512 threads issues iters * 16
  * v_mfma_f32_32x32x16_bf16 instructions on register-resident operands (no LDS, no

@@ -274,13 +274,15 @@ mst_status run_forward_chunks(const Plan& p, const __bf16* H, const __bf16* W, c
   const size_t stride = (size_t)p.fwd_group_rows;
   for (int64_t g0 = 0; g0 < p.S; g0 += p.fwd_group_rows) {
     const int64_t g_rows = (p.S - g0) < p.fwd_group_rows ? (p.S - g0) : p.fwd_group_rows;
-    for (int64_t r0 = g0; r0 < g0 + g_rows; r0 += p.C) {
-      const int rows = (int)((p.S - r0) < p.C ? (p.S - r0) : p.C);
-      const int n_st = (rows + kTile - 1) / kTile;
+    {
+      // One launch for the group's mini-sequences.  Rows are independent and no logits are stored, so the row tiles
+      // of the launch need not respect the boundaries between the mini-sequences of the group: a mini-sequence
+      // shorter than a 256-row tile costs no idle tile rows, and every row's result is bit-identical for every M.
+      const int n_st = (int)((g_rows + kTile - 1) / kTile);
       Scope sc(st, MST_K_FWD_GEMM_LSE);
-      hipLaunchKernelGGL(k_fwd_gemm_lse, dim3(xcd_grid(n_st * p.n_vt)), dim3(kThreads), kLdsBytes, st,
-                         H + r0 * p.d, W, labels + r0, rows, (int)p.d, (int)p.V, n_st, p.n_vt,
-                         part + (r0 - g0), stride, tgt + (r0 - g0));
+      hipLaunchKernelGGL(k_fwd_gemm_lse, dim3(xcd_grid_2d(p.n_vt, n_st)), dim3(kThreads), kLdsBytes, st,
+                         H + g0 * p.d, W, labels + g0, (int)g_rows, (int)p.d, (int)p.V, n_st, p.n_vt,
+                         part, stride, tgt);
     }
     {
       Scope sc(st, MST_K_LSE_FINALIZE);
@@ -598,6 +600,24 @@ mst_status mst_bwd_schedule_info_for(int64_t S, int64_t d, int64_t V, int32_t M,
   info[6] = (int64_t)p.est_pairs_us;
   info[7] = (int64_t)p.est_blocks_us;
   return MST_OK;
+}
+
+int32_t mst_tile_of_workgroup(int32_t n_slow, int32_t n_fast, int32_t order, int32_t workgroup, int32_t* slow,
+                              int32_t* fast) {
+  if (n_slow < 1 || n_fast < 1 || workgroup < 0 || !slow || !fast || order < 0 || order > 1) return -1;
+  if (workgroup >= xcd_grid_2d(n_slow, n_fast)) return -1;
+  int s = 0, f = 0;
+  const bool ok = order == 0
+      ? xcd_tile_of_block<kXcdRectSlow, kXcdRectFast, kXcdSuper>(workgroup, n_slow, n_fast, &s, &f)
+      : xcd_tile_of_block<kXcdRectSlow, kXcdRectFast, kXcdRectFast>(workgroup, n_slow, n_fast, &s, &f);
+  *slow = s;
+  *fast = f;
+  return ok ? 1 : 0;
+}
+
+int32_t mst_tile_grid(int32_t n_slow, int32_t n_fast) {
+  if (n_slow < 1 || n_fast < 1 || (int64_t)xcd_grid_2d(n_slow, 1) * n_fast > 0x7fffffff) return -1;
+  return xcd_grid_2d(n_slow, n_fast);
 }
 
 mst_status mst_profile_enable(int enable) {

@@ -73,31 +73,53 @@ __device__ __forceinline__ int xcd_work_item(int total) {
 }
 inline int xcd_grid(int total) { return kNumXcd * ((total + kNumXcd - 1) / kNumXcd); }
 
-// Remap for a 2-D tile space (n_slow x n_fast) in which every tile reads one panel per coordinate:
-// each XCD owns a contiguous range of the slow coordinate and walks it in groups of kFastGroup fast
-// tiles, so that the 32 workgroups resident on an XCD form an 8 x 4 rectangle of tiles (12 distinct
-// panels for 32 workgroups) instead of a 2 x 16 strip (18 panels).  Returns false for padding workgroups.
-constexpr int kFastGroup = 4;
-__device__ __forceinline__ bool xcd_tile_2d(int n_slow, int n_fast, int* slow, int* fast, int block = -1) {
-  if (block < 0) block = blockIdx.x;       // a kernel that serves several tile spaces passes its own index
-  const int x = block % kNumXcd, q = block / kNumXcd;
+// Remap for a 2-D tile space (n_slow x n_fast) in which every tile reads one panel per coordinate.  Each XCD owns a
+// contiguous range of the slow coordinate.  Its 32 resident workgroups (one "round") form a kRectSlow x kRectFast
+// rectangle of tiles (12 distinct panels for 32 workgroups; a 1 x 32 strip would read 33), and the rounds walk
+//   for each super-group of kSuper fast tiles:  for each band of kRectSlow slow tiles of the XCD:  for each kRectFast
+//   fast tiles of the super-group
+// With kSuper > kRectFast consecutive rounds keep the same slow panels while the fast panels of a super-group, which
+// all XCDs walk at the same time, stay in the memory-side cache for the XCD's whole slow range: in the forward kernel
+// (slow = vocabulary, fast = rows; W, 1 GB, cannot stay in any cache) W is streamed from HBM once per 8192 rows
+// instead of once per 1024 (forward pass -2.4 % against kSuper = kRectFast, -6 % against 8 x 4 rectangles walked
+// fast-group by fast-group).  With kSuper = kRectFast the fast panels are the ones kept from round to round; the
+// dlogits kernel, whose window of W is in the memory-side cache anyway, is 2 % faster that way.  Returns false for
+// padding workgroups.
+template <int kRectSlow, int kRectFast, int kSuper>
+__host__ __device__ inline bool xcd_tile_of_block(int block, int n_slow, int n_fast, int* slow, int* fast) {
+  static_assert(kSuper % kRectFast == 0, "a super-group is a whole number of rectangles");
+  const int x = block % kNumXcd;
+  int q = block / kNumXcd;
   const int spx = (n_slow + kNumXcd - 1) / kNumXcd;          // slow tiles per XCD
   if (q >= spx * n_fast) return false;
-  const int full = n_fast / kFastGroup, rem = n_fast - full * kFastGroup;
-  const int per_full = spx * kFastGroup;
-  int sl, f;
-  if (q < full * per_full) {
-    const int g = q / per_full, r = q - g * per_full;
-    sl = r / kFastGroup;
-    f = g * kFastGroup + (r - sl * kFastGroup);
-  } else {
-    const int r = q - full * per_full;
-    sl = r / rem;
-    f = full * kFastGroup + (r - sl * rem);
-  }
-  *slow = x * spx + sl;
-  *fast = f;
+  const int per_super = spx * kSuper;                        // super-group of fast tiles
+  const int sup = q / per_super;
+  q -= sup * per_super;
+  const int f0 = sup * kSuper;
+  const int fs = n_fast - f0 < kSuper ? n_fast - f0 : kSuper;
+  const int per_band = kRectSlow * fs;                       // band of kRectSlow slow tiles
+  const int band = q / per_band;
+  q -= band * per_band;
+  const int s0 = band * kRectSlow;
+  const int ss = spx - s0 < kRectSlow ? spx - s0 : kRectSlow;
+  const int per_rect = ss * kRectFast;                       // rectangle: ss x (up to kRectFast) tiles
+  const int rect = q / per_rect;
+  q -= rect * per_rect;
+  const int g0 = rect * kRectFast;
+  const int gs = fs - g0 < kRectFast ? fs - g0 : kRectFast;
+  const int sl = q / gs;
+  *slow = x * spx + s0 + sl;
+  *fast = f0 + g0 + (q - sl * gs);
   return *slow < n_slow;
+}
+constexpr int kXcdRectSlow = 4, kXcdRectFast = 8, kXcdSuper = 32;
+// a kernel that serves several tile spaces passes its own workgroup index as `block`
+__device__ __forceinline__ bool xcd_tile_2d(int n_slow, int n_fast, int* slow, int* fast, int block = -1) {
+  return xcd_tile_of_block<kXcdRectSlow, kXcdRectFast, kXcdSuper>(block < 0 ? (int)blockIdx.x : block, n_slow, n_fast, slow, fast);
+}
+// the same with the fast panels kept from round to round
+__device__ __forceinline__ bool xcd_tile_2d_fast_major(int n_slow, int n_fast, int* slow, int* fast) {
+  return xcd_tile_of_block<kXcdRectSlow, kXcdRectFast, kXcdRectFast>((int)blockIdx.x, n_slow, n_fast, slow, fast);
 }
 inline int xcd_grid_2d(int n_slow, int n_fast) { return kNumXcd * ((n_slow + kNumXcd - 1) / kNumXcd) * n_fast; }
 
@@ -184,9 +206,8 @@ __global__ __launch_bounds__(kThreads) void k_fwd_gemm_lse(
     int rows, int d, int V, int n_st, int n_vt, float2* __restrict__ part, size_t part_stride,
     float* __restrict__ tgt) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  const int w = xcd_work_item(n_st * n_vt);
-  if (w < 0) return;
-  const int vt = w / n_st, st = w - vt * n_st;
+  int vt, st;                                        // an XCD's resident workgroups: 4 vocabulary x 8 row tiles
+  if (!xcd_tile_2d(n_vt, n_st, &vt, &st)) return;
   const int v0 = vt * kTile, s0 = st * kTile;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -351,8 +372,8 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dlogits(
     const float* __restrict__ lse_c, int rows, int d, int V, int v_base, int V_all, int ignore_index, int n_st, int n_vt,
     __bf16* __restrict__ G, int ldg) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  int vt, st;                                        // an XCD's resident workgroups: 8 vocabulary x 4 row tiles
-  if (!xcd_tile_2d(n_vt, n_st, &vt, &st)) return;
+  int vt, st;                                        // an XCD's resident workgroups: 4 vocabulary x 8 row tiles
+  if (!xcd_tile_2d_fast_major(n_vt, n_st, &vt, &st)) return;
   const int v0 = vt * kTile, s0 = st * kTile;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);

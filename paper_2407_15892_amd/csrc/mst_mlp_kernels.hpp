@@ -241,7 +241,8 @@ __global__ __launch_bounds__(kThreads) void k_mlp_dw3(DwProblems ps, int rows) {
   if (b >= ps.p[0].grid) { b -= ps.p[0].grid; which = 1; if (b >= ps.p[1].grid) { b -= ps.p[1].grid; which = 2; } }
   const DwProblem& q = ps.p[which];
   int vt, jt;
-  if (!xcd_tile_2d(q.n_vt, q.n_jt, &vt, &jt, b)) return;
+  // 8 x 4 rectangles walked group by group of 4 fast tiles (measured 0.7 % faster here than the LM-head's 4 x 8 bands)
+  if (!xcd_tile_of_block<8, 4, 4>(b, q.n_vt, q.n_jt, &vt, &jt)) return;
   if (kStoreOnly) dw_tile16(q.G, q.ldg, q.ldg, q.H, q.ldh, rows, q.d, q.V, vt, jt, 0, 1.0f, q.dW, q.d, smem);
   else dw_tile(q.G, q.ldg, q.ldg, q.H, q.ldh, rows, q.d, q.V, vt, jt, 1, 1.0f, q.dW, q.d, smem);
 }

@@ -255,3 +255,43 @@ def test_static_scratch_forward_rejects_what_does_not_fit(mst):
     assert mst.binding.mst_workspace_bytes_status(S, d, V, M) == 0          # the shape itself is accepted
     rc = lib.mst_lmhead_ce_fwd_static(fake, fake, fake, S, d, V, -100, M, fake, None, None, None)
     assert rc == -4 and "workspace" in mst.mst_strerror(rc)
+
+
+def test_workgroup_to_tile_map_is_a_bijection(mst):
+    """The GEMM kernels' XCD-aware map from the linear workgroup id to a tile (the same function, called on the
+    host): every tile of the space is hit by exactly one workgroup, padding workgroups report themselves, each XCD
+    (workgroup id mod 8) owns a contiguous range of the slow coordinate, and the 32 workgroups that are resident
+    on an XCD at a time read at most 12 distinct operand panels."""
+    lib = mst.load_library()
+    lib.mst_tile_grid.restype = ctypes.c_int32
+    lib.mst_tile_of_workgroup.restype = ctypes.c_int32
+    s, f = ctypes.c_int32(), ctypes.c_int32()
+    shapes = [(1, 1), (3, 5), (8, 4), (9, 33), (63, 32), (501, 4), (16, 16), (63, 16), (125, 64), (32, 16), (7, 100)]
+    for n_slow, n_fast, order in [sh + (o,) for sh in shapes for o in (0, 1)]:
+        grid = lib.mst_tile_grid(n_slow, n_fast)
+        assert grid == 8 * -(-n_slow // 8) * n_fast
+        seen = {}
+        per_xcd = {x: [] for x in range(8)}
+        for b in range(grid):
+            rc = lib.mst_tile_of_workgroup(n_slow, n_fast, order, b, ctypes.byref(s), ctypes.byref(f))
+            assert rc in (0, 1)
+            if rc == 0:
+                per_xcd[b % 8].append(None)                         # a padding workgroup still takes a slot of its round
+            if rc == 1:
+                assert 0 <= s.value < n_slow and 0 <= f.value < n_fast
+                assert (s.value, f.value) not in seen, (n_slow, n_fast, b)
+                seen[(s.value, f.value)] = b
+                per_xcd[b % 8].append((s.value, f.value))
+        assert len(seen) == n_slow * n_fast
+        spx = -(-n_slow // 8)
+        for x, tiles in per_xcd.items():
+            assert all(x * spx <= t[0] < (x + 1) * spx for t in tiles if t)
+            for r0 in range(0, len(tiles), 32):                     # one round of resident workgroups
+                rnd = [t for t in tiles[r0:r0 + 32] if t]
+                panels = len({t[0] for t in rnd}) + len({t[1] for t in rnd})
+                if spx >= 4 and n_fast >= 8:
+                    assert panels <= 13, (n_slow, n_fast, x, r0, panels)
+    assert lib.mst_tile_of_workgroup(4, 4, 0, -1, ctypes.byref(s), ctypes.byref(f)) == -1
+    assert lib.mst_tile_of_workgroup(4, 4, 0, 10 ** 6, ctypes.byref(s), ctypes.byref(f)) == -1
+    assert lib.mst_tile_of_workgroup(4, 4, 2, 0, ctypes.byref(s), ctypes.byref(f)) == -1
+    assert lib.mst_tile_grid(0, 4) == -1
