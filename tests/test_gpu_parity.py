@@ -297,6 +297,7 @@ def schedule():
     (1400, 72, 5000, 12, 2, 4),     # ragged second row block (768 + 632 rows)
     (1800, 136, 2900, 12, 3, 4),    # three row blocks: dW stored, accumulated, accumulated and scaled
     (600, 64, 70000, 1, 1, 2),      # wide windows, V not a multiple of 8
+    (9000, 64, 600, 3, 2, 2),       # two row blocks of more than 4096 rows each (long contraction in the dW pass that reads dW back)
 ])
 @pytest.mark.parametrize("fused", [False, True])
 def test_block_schedule_matches_oracle(schedule, S, d, V, M, blocks, windows, fused):
@@ -366,6 +367,16 @@ def test_dlogits_block_left_in_the_workspace_matches_oracle(schedule, which):
     assert in_block.sum() > 10
     lab = G[np.flatnonzero(in_block), (y - v0)[in_block]]
     assert np.all(lab < 0.0) and np.all(lab >= -1.0) and lab.mean() < -0.9, "label entries are p - 1"
+
+
+def test_pair_schedule_with_long_pairs(schedule):
+    """Two pairs of mini-sequences of 9000 rows each: the second pair's dW pass adds to the stored sums over a long
+    contraction (141 K steps)."""
+    import paper_2407_15892_amd as mst
+    schedule(mst.BWD_SCHEDULE_PAIRS)
+    cfg = mi.custom_config(18000, 64, 600, 4, index=431, w_std=0.3, ignore_frac=0.05, label_dist="zipf")
+    assert mst.mst_bwd_schedule_info(cfg.S, cfg.d, cfg.V, cfg.M)["schedule"] == mst.BWD_SCHEDULE_PAIRS
+    _check_full(mi.make_inputs(cfg), grad_loss=1.25)
 
 
 def test_block_and_pair_schedules_agree_and_repeat_bit_for_bit(schedule):
