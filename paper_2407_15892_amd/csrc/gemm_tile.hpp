@@ -204,13 +204,18 @@ __device__ __forceinline__ void gemm_mainloop_pp(typename C::Acc (&acc)[C::TA][C
     __builtin_amdgcn_sched_barrier(0);
     // ---- compute phase
     __builtin_amdgcn_s_setprio(1);
+    // Serpentine order over the B-side tiles: between any two consecutive MFMAs one of the two operands stays in
+    // place (in plain row-major order both change at every row change).  On this power-limited chip fewer operand
+    // changes are measurably cheaper: -0.55 % of the LM-head step, same-box A/B.
 #pragma unroll
     for (int kk = 0; kk < C::kKK; ++kk)
 #pragma unroll
       for (int t = 0; t < C::TA; ++t)
 #pragma unroll
-        for (int u = 0; u < C::TB; ++u)
+        for (int uu = 0; uu < C::TB; ++uu) {
+          const int u = (t & 1) ? C::TB - 1 - uu : uu;
           acc[t][u] = C::mma(a[kk][t], b[kk][u], acc[t][u]);
+        }
     __builtin_amdgcn_s_setprio(0);
     if (group == 0) wait_vmcnt<kAhead>();      // group 0 opens step kt + 1 right after this phase
     __builtin_amdgcn_sched_barrier(0);
