@@ -104,6 +104,9 @@ void choose_schedule(Plan* p, int forced) {
     const int win_tiles = (n_vt + n_win - 1) / n_win;
     const int n_win_eff = (n_vt + win_tiles - 1) / win_tiles;
     if (n_win_eff != n_win) continue;                       // same partition as a smaller count
+#ifdef MST_FORCE_WINDOWS                                    // measurement builds: rank by measurement, not by the model
+    if (n_win != MST_FORCE_WINDOWS) continue;
+#endif
     const int64_t ldg_w = (int64_t)win_tiles * kTile;
     const int64_t per_row = ldg_w * 2 + d * 4;
     if (p->b_total < 256 + (size_t)per_row * kTile) continue;
