@@ -84,6 +84,27 @@ def test_mini_sequence_invariance_on_gpu(M):
     _check_full(mi.make_inputs(1), M=M)
 
 
+def test_forward_is_bit_identical_for_every_number_of_mini_sequences():
+    """The forward stores no logits, so its row tiles ignore mini-sequence boundaries and every row's arithmetic is
+    the same whatever M is: lse and loss agree bit for bit between M = 1, ragged M, one row per mini-sequence, and
+    several merge groups (the static-scratch entry point shortens the groups; M = 37 with V = 70000 also splits them
+    in the workspace entry point)."""
+    import torch
+    DeviceRun, _ = _harness()
+    inp = mi.make_inputs(mi.custom_config(1111, 72, 70000, 1, index=440, w_std=0.3, ignore_frac=0.07, label_dist="zipf"))
+    ref = None
+    for M in (1, 2, 7, 37, 300, 1111):
+        run = DeviceRun(inp, M=M)
+        loss, lse, nv = run.forward()
+        bits = (np.float32(loss).view(np.uint32), lse.astype(np.float32).view(np.uint32), nv)
+        if ref is None:
+            ref = bits
+            ref_o = orc.lmhead_ce_forward(inp.H_f64(), inp.W_f64(), inp.labels, inp.ignore_index)
+            assert nv == ref_o[3] and abs(loss - ref_o[0]) <= LOSS_RTOL * abs(ref_o[0])
+        else:
+            assert bits[0] == ref[0] and np.array_equal(bits[1], ref[1]) and bits[2] == ref[2], f"M = {M}"
+
+
 def test_dW_and_dH_bit_identical_across_runs():
     DeviceRun, _ = _harness()
     import torch
