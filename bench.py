@@ -231,6 +231,9 @@ def main() -> int:
                     help="LM-head path: override the number of mini-sequences M of the chosen configuration (sweeps)")
     ap.add_argument("--rows", type=int, default=None,
                     help="LM-head path: override the number of tokens S (same value distributions, own seed stream)")
+    ap.add_argument("--operands", choices=("recipe", "zero"), default="recipe",
+                    help="LM-head path: 'zero' replaces H and W by zeros on the device (same kernels, same traffic, the "
+                         "matrix cores multiply zeros): a power probe, NOT a benchmark line")
     ap.add_argument("--cpu-sample-rows", type=int, default=4096)
     ap.add_argument("--bwd-schedule", choices=("auto", "pairs", "blocks", "blocks_fused"), default="auto",
                     help="order of the LM-head backward pass (default: the library's own choice)")
@@ -278,6 +281,9 @@ def main() -> int:
 
     H = to_device_bf16(inp.H_bits)
     W = to_device_bf16(inp.W_bits)
+    if args.operands == "zero":
+        H.zero_()
+        W.zero_()
     labels = torch.from_numpy(inp.labels).cuda()
     fwd_bytes, bwd_bytes = mst.mst_workspace_bytes(S, d, V, M)
     ws = torch.empty(max(fwd_bytes, bwd_bytes), dtype=torch.uint8, device="cuda")
@@ -368,7 +374,8 @@ def main() -> int:
         "metric": "LM-head+CE fwd+bwd TFLOP/s (8*S*d*V executed flop incl. recomputation)",
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": "bf16",
+        "data": "synthetic" if args.operands == "recipe" else "all-zero H and W (power probe, not a benchmark line)",
         "step_ms": {"median": per_step[len(per_step) // 2] if len(per_step) % 2 else
                     0.5 * (per_step[len(per_step) // 2 - 1] + per_step[len(per_step) // 2]),
                     "min": per_step[0], "max": per_step[-1], "n": len(per_step),
@@ -388,7 +395,7 @@ def main() -> int:
         "roofline": roofline, "kernels": kernels, "input_generation_s": gen_s,
     }
     out["empirical_mfma_peak"] = mfma_probe(mst, torch)
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.operands == "recipe":
         out["cpu_baseline"] = cpu_baseline(inp, args.cpu_sample_rows)
     print(json.dumps(out))
     return 0
