@@ -4,7 +4,7 @@ exactly (one streamed fp64 forward pass), exact dH on a stratified sample of tok
 in every 256-row tile, so every row block, row tile and XCD rectangle of the launch is hit) and exact
 dW on a stratified sample of vocabulary rows (at least one in every 256-entry vocabulary tile, so every
 vocabulary window and the ragged last tile are hit); properties that hold at any size cover the rest:
-columns of dW sum to ~0, ignored rows of dH are exactly 0, dW is bit-identical across runs.
+columns of dW sum to ~0, ignored rows of dH are exactly 0, loss, lse, dW and dH are bit-identical across runs.
 
 What the tolerances can and cannot see.  Against max|reference| over the tensor (the stated bar) the
 softmax part of the gradients is invisible at configurations 2 and 3: with logit sigma = 0.08 the softmax is
@@ -88,6 +88,7 @@ def run_and_check(cfg, tag, expect_softmax_visible_globally):
     loss, lse, nv = run.forward()
     dH, dW = run.backward()
     dW_first = dW.clone()
+    dH_first = dH.clone()
     print(f"{tag}: inputs+gpu {time.time() - t0:.1f}s", flush=True)
 
     # --- oracle: exact loss and lse for all rows, gradients on stratified samples
@@ -148,10 +149,12 @@ def run_and_check(cfg, tag, expect_softmax_visible_globally):
     col_sums = dW.double().sum(dim=0).abs().max().item()
     # rows of bf16 dlogits sum to zero within 2^-8 relative steps; bound by mean|H| * 2^-7 per unit grad_loss
     assert col_sums <= 2.0 ** -7 * max(cfg.h_std, 1e-3), col_sums
-    # bit-identical dW on a second run
-    run.forward()
-    _, dW2 = run.backward()
+    # bit-identical loss, lse, dW and dH on a second run
+    loss2, lse2, _ = run.forward()
+    dH2, dW2 = run.backward()
+    assert loss2 == loss and np.array_equal(lse2, lse)
     assert torch.equal(dW_first.view(torch.int32), dW2.view(torch.int32))
+    assert torch.equal(dH_first.view(torch.int16), dH2.view(torch.int16))
 
     # --- the other order of the backward pass against the same references
     other = mst.BWD_SCHEDULE_BLOCKS if sched["schedule"] == mst.BWD_SCHEDULE_PAIRS else mst.BWD_SCHEDULE_PAIRS
