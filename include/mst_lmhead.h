@@ -177,6 +177,9 @@ mst_status mst_lmhead_ce_fwd(const void* H, const void* W, const int32_t* labels
  *     call's contents; nothing in it has to start at zero (every word a kernel
  *     reads has been written earlier in the same call).  Calls that overlap on
  *     one GPU (two streams, two threads) race on it: serialise them.
+ *   - The first call on a device takes the array's device address (and, like the
+ *     other calls, sets kernel attributes): make it outside stream capture; every
+ *     later call only enqueues kernels and can be captured.
  *   - Other errors as for mst_lmhead_ce_fwd; MST_ERR_LAUNCH also if the array's
  *     device address cannot be obtained.
  */

@@ -62,3 +62,36 @@ def test_static_scratch_forward_matches_the_workspace_forward_twice():
         assert ref_nv == nv1
         assert abs(loss1 - ref_loss) <= 1e-3 * abs(ref_loss)
         assert np.abs(lse1_f - ref_lse).max() <= 2e-3 * max(1.0, np.abs(ref_lse).max())
+
+
+def test_static_scratch_forward_replays_from_a_hip_graph():
+    """The audience of this entry point: code under HIP graph capture.  After one eager call on the device (which takes
+    the array's address and sets kernel attributes) the call is captured and every replay reproduces the eager bits."""
+    import torch
+    import paper_2407_15892_amd as mst
+    inp = mi.make_inputs(mi.custom_config(900, 136, 5000, 3, index=342, w_std=0.3, ignore_frac=0.05))
+    H, W = mi.to_device_bf16(inp.H_bits), mi.to_device_bf16(inp.W_bits)
+    y = torch.from_numpy(inp.labels).cuda()
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    lse = torch.empty(inp.cfg.S, dtype=torch.float32, device="cuda")
+    nv = torch.zeros(1, dtype=torch.int64, device="cuda")
+
+    def call():
+        mst.mst_lmhead_ce_fwd_static(H, W, y, inp.ignore_index, inp.cfg.M, loss, lse, nv)
+
+    call()
+    torch.cuda.synchronize()
+    ref = (loss.clone(), lse.clone(), nv.clone())
+    assert int(ref[2]) == inp.n_valid
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    for _ in range(3):
+        loss.fill_(float("nan")); lse.fill_(float("nan")); nv.fill_(-5)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(loss.view(torch.int32), ref[0].view(torch.int32))
+        assert torch.equal(lse.view(torch.int32), ref[1].view(torch.int32))
+        assert int(nv) == int(ref[2])
+    del graph
