@@ -326,11 +326,14 @@ __global__ __launch_bounds__(kFinRows * kFinGroups) void k_lse_finalize(
     l = l * fast_exp2((m - mm) * kLog2e) + p.y * fast_exp2((p.x - mm) * kLog2e);
     m = mm;
   }
-  const float lse = m + __builtin_amdgcn_logf(l) * kLn2;   // v_log_f32 is log2
+  const float log_l = __builtin_amdgcn_logf(l) * kLn2;     // v_log_f32 is log2
+  const float lse = m + log_l;
   const int y = labels_c[s];
   const bool valid = (y != ignore_index) && ((unsigned)y < (unsigned)V);
   if (lse_c) lse_c[s] = lse;
-  if (nll_c) nll_c[s] = valid ? lse - tgt[s] : 0.f;
+  // nll = lse - z_y as (m - z_y) + log l: for a confidently predicted label (z_y = m or close to it) the first term is
+  // exact and the small second one keeps its relative precision, where m + log l would round it to the grid of m
+  if (nll_c) nll_c[s] = valid ? (m - tgt[s]) + log_l : 0.f;
 }
 
 // loss = sum(nll) / n_valid, fixed summation order, fp64 accumulation.  One workgroup.
@@ -402,7 +405,9 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dlogits(
     const int y_abs = labels_c[s_local];
     const bool valid = (y_abs != ignore_index) && ((unsigned)y_abs < (unsigned)V_all);
     const int y = y_abs - v_base;                    // position in the window; outside [0, V) if the label is elsewhere
-    const float lb = lse_c[s_local] * kLog2e;
+    // z - lse is formed first and scaled afterwards: where a class dominates (z close to lse) the difference is exact,
+    // so p - 1 at a confidently predicted label keeps full precision, and a one-class vocabulary gives exactly 0
+    const float lse_s = lse_c[s_local];
     char* srow = smem + row * kStageRow + (wa * 128 + 32 * (lane >> 4)) * 2;
 #pragma unroll
     for (int p = 0; p < kTA16 / 2; ++p) {            // tiles 2p and 2p + 1: entries va + 8p .. + 7
@@ -410,7 +415,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dlogits(
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const int v = va + 8 * p + e;
-        float gval = fast_exp2(acc[2 * p + (e >> 2)][u][e & 3] * kLog2e - lb);
+        float gval = fast_exp2((acc[2 * p + (e >> 2)][u][e & 3] - lse_s) * kLog2e);
         if (v == y) gval -= 1.0f;
         if (!valid || v >= V) gval = 0.f;
         o[e] = (__bf16)gval;
