@@ -105,6 +105,23 @@ def test_seeded_random_shapes_match_oracle(schedule, S, d, V, M):
     _check_full(inp, grad_loss=0.9, use_lse=False, scale_floor=floor)
 
 
+def test_confidently_predicted_labels():
+    """The regime of a trained model: for most rows the label is the class with the largest logit and the softmax is
+    sharp (logit sigma about 9), so p_label is close to 1, the per-row loss is small and p - 1 is a small difference.
+    Loss, lse, dH and dW against the oracle at the usual tolerances."""
+    cfg = mi.custom_config(900, 128, 3000, 3, index=450, w_std=0.8, ignore_frac=0.05)
+    inp = mi.make_inputs(cfg)
+    z = orc.logits_f64(inp.H_f64(), inp.W_f64())
+    rng = np.random.default_rng(450)
+    take = (rng.random(cfg.S) < 0.8) & (inp.labels != inp.ignore_index)
+    inp.labels[take] = z.argmax(axis=1)[take].astype(np.int32)
+    run, ref, (loss, eH, eW) = _check_full(inp, grad_loss=1.0)
+    p_label = np.exp(z[take, inp.labels[take]] - ref["lse"][take])
+    print(f"confident labels: loss {loss:.4f}, median p_label {np.median(p_label):.4f}, dH err {eH:.2e}, dW err {eW:.2e}")
+    assert np.median(p_label) > 0.7
+    _check_full(inp, grad_loss=1.0, use_lse=False)
+
+
 def test_forward_is_bit_identical_for_every_number_of_mini_sequences():
     """The forward stores no logits, so its row tiles ignore mini-sequence boundaries and every row's arithmetic is
     the same whatever M is: lse and loss agree bit for bit between M = 1, ragged M, one row per mini-sequence, and
