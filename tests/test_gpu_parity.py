@@ -122,6 +122,16 @@ def test_confidently_predicted_labels():
     _check_full(inp, grad_loss=1.0, use_lse=False)
 
 
+def test_huge_logits_do_not_overflow():
+    """Logits of several hundred in magnitude (sigma about 70): the maximum is taken out before every exponential, in
+    the per-tile partials, in their merge and in dlogits, so nothing overflows and the one-hot-like softmax comes out."""
+    cfg = mi.custom_config(520, 64, 1100, 2, index=451, h_std=3.0, w_std=3.0, ignore_frac=0.05)
+    inp = mi.make_inputs(cfg)
+    run, ref, (loss, eH, eW) = _check_full(inp)
+    assert np.abs(ref["lse"]).max() > 150.0
+    print(f"huge logits: loss {loss:.3f}, max |lse| {np.abs(ref['lse']).max():.1f}, dH err {eH:.2e}, dW err {eW:.2e}")
+
+
 def test_forward_is_bit_identical_for_every_number_of_mini_sequences():
     """The forward stores no logits, so its row tiles ignore mini-sequence boundaries and every row's arithmetic is
     the same whatever M is: lse and loss agree bit for bit between M = 1, ragged M, one row per mini-sequence, and
