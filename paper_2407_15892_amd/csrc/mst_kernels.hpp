@@ -397,6 +397,16 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dlogits(
   // over all banks), then every wave instruction writes two whole 512-byte rows.
   constexpr int kStageRow = kTile * 2 + 16;
   const int va = v0 + wa * 128 + 32 * (lane >> 4);   // this lane's 32 consecutive vocabulary entries start here
+  if (v0 + kTile > V) {                              // ragged last vocabulary tile: entries >= V must come out as 0
+#pragma unroll
+    for (int t = 0; t < kTA16; ++t)
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        if (va + 4 * t + r >= V) {
+#pragma unroll
+          for (int u = 0; u < kTB16; ++u) acc[t][u][r] = kMasked;
+        }
+  }
 #pragma unroll
   for (int u = 0; u < kTB16; ++u) {
     const int row = wb * 64 + 16 * u + (lane & 15);
@@ -404,23 +414,32 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dlogits(
     if (s_local >= rows) continue;
     const int y_abs = labels_c[s_local];
     const bool valid = (y_abs != ignore_index) && ((unsigned)y_abs < (unsigned)V_all);
-    const int y = y_abs - v_base;                    // position in the window; outside [0, V) if the label is elsewhere
     // z - lse is formed first and scaled afterwards: where a class dominates (z close to lse) the difference is exact,
-    // so p - 1 at a confidently predicted label keeps full precision, and a one-class vocabulary gives exactly 0
-    const float lse_s = lse_c[s_local];
+    // so p - 1 at a confidently predicted label keeps full precision, and a one-class vocabulary gives exactly 0.
+    // An ignored row takes lse = +infinity: every p is then exp2(-infinity) = 0 without a select per element, and
+    // its label index is moved out of range so that nothing is subtracted.
+    const float lse_s = valid ? lse_c[s_local] : __builtin_inff();
+    const int y_lane = valid ? y_abs - v_base - va : -1;   // the label's position among this lane's 32 entries, if it is there
     char* srow = smem + row * kStageRow + (wa * 128 + 32 * (lane >> 4)) * 2;
 #pragma unroll
     for (int p = 0; p < kTA16 / 2; ++p) {            // tiles 2p and 2p + 1: entries va + 8p .. + 7
       bf16x8 o;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int v = va + 8 * p + e;
-        float gval = fast_exp2((acc[2 * p + (e >> 2)][u][e & 3] - lse_s) * kLog2e);
-        if (v == y) gval -= 1.0f;
-        if (!valid || v >= V) gval = 0.f;
-        o[e] = (__bf16)gval;
-      }
+      for (int e = 0; e < 8; ++e)
+        o[e] = (__bf16)fast_exp2((acc[2 * p + (e >> 2)][u][e & 3] - lse_s) * kLog2e);
       *reinterpret_cast<bf16x8*>(srow + 16 * p) = o;
+    }
+    // The label's entry, p - 1, is patched in afterwards by the one lane that holds it (a lane holds 32 of the V
+    // entries of its row, so for most waves nobody does and the branch is skipped): a compare and a select per
+    // element of every row would cost a third of this epilogue's instructions.
+    if ((unsigned)y_lane < 32u) {
+      float z_y = 0.f;
+#pragma unroll
+      for (int t = 0; t < kTA16; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (4 * t + r == y_lane) z_y = acc[t][u][r];
+      *reinterpret_cast<__bf16*>(srow + 2 * y_lane) = (__bf16)(fast_exp2((z_y - lse_s) * kLog2e) - 1.0f);
     }
   }
   __syncthreads();
