@@ -156,9 +156,14 @@ struct PanelKS {
 // both) the matrix pipe was busy 75 % of the clocks, with loads that are never waited for 98 %.
 // Loads are always issued, also past the end of K: there they are out of range and write zeros into a stage
 // nobody reads.
-template <class C, class PA, class PB>
+struct NoHook { __device__ __forceinline__ void operator()() const {} };
+// `after_issue` runs once, after the first operand loads have been issued and before anything waits for them: a
+// kernel that has preloaded its accumulators from memory ties them off there, so that the latency of that preload
+// and the latency of the first panels pass together instead of one after the other.
+template <class C, class PA, class PB, class Hook = NoHook>
 __device__ __forceinline__ void gemm_mainloop_pp(typename C::Acc (&acc)[C::TA][C::TB], const PA& pa, const PB& pb,
-                                                 char* smem, int k_begin, int k_end, int group) {
+                                                 char* smem, int k_begin, int k_end, int group,
+                                                 Hook after_issue = Hook()) {
   static_assert(C::NSA == 3 && C::NSB == 2, "three A stages, two B stages");
   constexpr int kAhead = PA::SPW;              // loads of one A stage per wave: allowed in flight at a wait
   const uint32_t ldsA = lds_addr_of(smem), ldsB = ldsA + C::NSA * C::kPanelA;
@@ -167,6 +172,7 @@ __device__ __forceinline__ void gemm_mainloop_pp(typename C::Acc (&acc)[C::TA][C
   pa.issue(ldsA, k_begin);
   pb.issue(ldsB, k_begin);
   pa.issue(ldsA + C::kPanelA, k_begin + C::BK);
+  after_issue();
   wait_vmcnt<kAhead>();
   __builtin_amdgcn_s_barrier();
   if (group == 1) __builtin_amdgcn_s_barrier();

@@ -524,16 +524,21 @@ __device__ __forceinline__ void dh_tile(
           for (int r = 0; r < 4; ++r)
             acc[t][u][r] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(sums, lane_off[u] + row_off(t, r), 0, 0));
       }
+  }
+  // The preloaded sums are tied off behind the first operand loads (see gemm_mainloop_pp), not in front of them --
+  // on every path, also where nothing was preloaded: behind a condition the compiler would carry "loads pending"
+  // past it on the other path and wait for them in front of the MFMAs of every K step.
+  auto tie_off = [&]() {
 #pragma unroll
     for (int t = 0; t < kTA16; ++t)
 #pragma unroll
       for (int u = 0; u < kTB16; ++u) asm volatile("" : "+v"(acc[t][u]));
-  }
+  };
   PanelKC16<Tile16, kTile, kTA16, false> pa;
   PanelKS16<Tile16, kTile, kTB16> pb;
   pa.init(G + (size_t)s0 * ldg, ldg, rows - s0, ldg, wave, lane, wa);
   pb.init(W + j0, d, V, d - j0, wave, lane, wb);
-  gemm_mainloop_pp<Tile16>(acc, pa, pb, smem, k_begin, k_end, wa);
+  gemm_mainloop_pp<Tile16>(acc, pa, pb, smem, k_begin, k_end, wa, tie_off);
 
   const bool to_bf16 = mode == kDhLast || (mode == kDhSplit && n_split == 1);
   if (!to_bf16) {
@@ -657,19 +662,23 @@ __device__ __forceinline__ void dw_tile(
           for (int r = 0; r < 16; ++r)
             acc[t][u][r] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(out, lane_off[u] + row_off(t, r), 0, kNonTemporal));
       }
-    // The compiler has to see these loads complete before the main loop: its own wait-count bookkeeping
-    // cannot see the loop's hand-placed waits, so it would otherwise wait for every outstanding load
-    // (the operand prefetches included) in front of the first MFMAs of every K step.
-#pragma unroll
-    for (int t = 0; t < kTA; ++t)
-#pragma unroll
-      for (int u = 0; u < kTB; ++u) asm volatile("" : "+v"(acc[t][u]));
   }
+  // The compiler has to see these loads complete before the first MFMA: its own wait-count bookkeeping cannot see
+  // the loop's hand-placed waits, so it would otherwise wait for every outstanding load (the operand prefetches
+  // included) in front of the first MFMAs of every K step.  The tie-off sits behind the first operand loads.
+  auto tie_off = [&]() {
+    if (accumulate) {
+#pragma unroll
+      for (int t = 0; t < kTA; ++t)
+#pragma unroll
+        for (int u = 0; u < kTB; ++u) asm volatile("" : "+v"(acc[t][u]));
+    }
+  };
   PanelKS<Tile, kTile, kTA> pa;
   PanelKS<Tile, kTile, kTB> pb;
   pa.init(G + v0, ldg, rows, g_cols - v0, wave, lane, wa);
   pb.init(Hc + j0, ldh, rows, d - j0, wave, lane, wb);
-  gemm_mainloop_pp<Tile>(acc, pa, pb, smem, 0, rows, wa);
+  gemm_mainloop_pp<Tile>(acc, pa, pb, smem, 0, rows, wa, tie_off);
 
   // scaled in place first: a store whose data sits in a reused temporary would have to wait for older stores
 #pragma unroll
