@@ -73,6 +73,37 @@ def mfma_probe(mst, torch):
     return out
 
 
+def library_gemm_yardstick(torch, H, W, S, d, V, reps=5):
+    """The path's contractions as unfused library GEMMs on the benchmark's own operands: logits = H W^T, then with the
+    full S x V softmax materialised in bf16 (which the path never does), dH = G W and dW = G^T H.  Medians of `reps`
+    launches each.  A plain head runs four of them per step (the logits twice when it recomputes) plus the softmax
+    passes this figure leaves out."""
+    Z = torch.empty((S, V), dtype=torch.bfloat16, device="cuda")
+    oH = torch.empty((S, d), dtype=torch.bfloat16, device="cuda")
+    oW = torch.empty((V, d), dtype=torch.bfloat16, device="cuda")
+
+    def med(fn):
+        fn()
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        ev[0].record()
+        for i in range(reps):
+            fn()
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        return sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(reps))[reps // 2]
+
+    res = {"logits": med(lambda: torch.matmul(H, W.t(), out=Z))}
+    for r0 in range(0, S, 2048):                       # G = softmax(logits), in place, block by block
+        Z[r0:r0 + 2048] = torch.softmax(Z[r0:r0 + 2048].float(), dim=1).to(torch.bfloat16)
+    res["dH"] = med(lambda: torch.matmul(Z, W, out=oH))
+    res["dW"] = med(lambda: torch.matmul(Z.t(), H, out=oW))
+    flop = 2.0 * S * d * V
+    return {"what": "torch.matmul bf16 (library GEMM), same H and W, G = bf16 softmax of the logits; median ms per GEMM",
+            "ms": res, "tflops": {k: flop / (v * 1e-3) / 1e12 for k, v in res.items()},
+            "four_gemms_ms": 2 * res["logits"] + res["dH"] + res["dW"]}
+
+
 def cpu_baseline(inp, sample_rows: int):
     """The fp64 oracle as it stands, timed on the host cores on the first `sample_rows` tokens."""
     import numpy as np
@@ -240,6 +271,10 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="do not bracket kernels with events inside the timed region")
+    ap.add_argument("--library-gemm", action="store_true",
+                    help="LM-head path: after the timed region also time the path's three contractions as plain library "
+                         "GEMMs (torch.matmul, bf16) on the same H and W and a materialised softmax: a yardstick for what "
+                         "the chip sustains on these shapes and this data, not part of the step")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one 1 GiB device-to-device copy, the known-size kernel the HBM counters are scaled by")
     args = ap.parse_args()
@@ -395,6 +430,9 @@ def main() -> int:
         "roofline": roofline, "kernels": kernels, "input_generation_s": gen_s,
     }
     out["empirical_mfma_peak"] = mfma_probe(mst, torch)
+    if args.library_gemm:
+        del ws, dW
+        out["library_gemm"] = library_gemm_yardstick(torch, H, W, S, d, V)
     if not args.no_cpu_baseline and args.operands == "recipe":
         out["cpu_baseline"] = cpu_baseline(inp, args.cpu_sample_rows)
     print(json.dumps(out))
