@@ -63,6 +63,19 @@ def test_ragged_shapes_match_oracle(S, d, I, M):
     _check(inp)
 
 
+@pytest.mark.parametrize("S,d,I,M", [
+    (57, 656, 1680, 4), (526, 704, 1944, 3), (1920, 320, 584, 1), (513, 144, 1776, 10), (255, 672, 920, 5),
+    (1151, 1008, 1184, 4), (2232, 1032, 512, 6), (7, 936, 1984, 5), (1498, 832, 416, 11), (512, 960, 512, 1),
+    (257, 704, 1632, 7), (1, 8, 2048, 1),
+])
+def test_seeded_random_shapes_match_oracle(S, d, I, M):
+    """Shapes drawn once from a seeded generator (S around the 255 / 256 / 257 / 512 / 513 tile edges and single rows,
+    d from 8 to 1032, I from 416 to 2048, M up to 11, so that d spans several tiles of the dX and weight-gradient
+    launches and the chunks are ragged): all five outputs against the oracle."""
+    w_std = (0.02, 0.05, 0.3)[(S + I) % 3]
+    _check(mi.make_mlp_inputs(mi.custom_mlp_config(S, d, I, M, index=300 + (S * 5 + I) % 89, w_std=w_std)))
+
+
 def test_large_activations_saturate_without_nan():
     # gate pre-activations with |g| up to ~60: exp2 overflows inside the logistic function and must give 0, not NaN
     inp = mi.make_mlp_inputs(mi.custom_mlp_config(256, 128, 256, 2, index=301, x_std=4.0, w_std=0.4))
