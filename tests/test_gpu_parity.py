@@ -105,6 +105,25 @@ def test_seeded_random_shapes_match_oracle(schedule, S, d, V, M):
     _check_full(inp, grad_loss=0.9, use_lse=False, scale_floor=floor)
 
 
+@pytest.mark.parametrize("S,d,V,M", [
+    (512, 8192, 1024, 2),        # d of 32 column tiles: K of the forward twice that of the benchmark shapes
+    (2, 32768, 16, 1),           # two rows, a very long contraction
+    (8, 64, 1000003, 1),         # a million classes for a handful of rows: 3907 vocabulary tiles, ragged last one
+    (1000003, 8, 8, 7),          # a million rows, smallest legal d: 3907 row tiles, chunks of 142858 rows
+    (70000, 8, 1024, 35000),     # two rows per mini-sequence
+])
+def test_extreme_aspect_ratios_match_oracle(schedule, S, d, V, M):
+    """Shapes far from the benchmark's, each dimension in turn much larger than the others: loss, lse, dH and dW against
+    the oracle under the automatic backward order and with the pair order forced."""
+    import paper_2407_15892_amd as mst
+    cfg = mi.custom_config(S, d, V, M, index=800 + (S + V) % 83, w_std=0.05, ignore_frac=0.1 if S > 20 else 0.0,
+                           label_dist="zipf" if V > 50 else "uniform")
+    inp = mi.make_inputs(cfg)
+    _check_full(inp)
+    schedule(mst.BWD_SCHEDULE_PAIRS)
+    _check_full(inp, use_lse=False)
+
+
 def test_confidently_predicted_labels():
     """The regime of a trained model: for most rows the label is the class with the largest logit and the softmax is
     sharp (logit sigma about 9), so p_label is close to 1, the per-row loss is small and p - 1 is a small difference.
