@@ -696,9 +696,16 @@ __device__ __forceinline__ void dw_tile(
     }
 }
 
+// A dW pass that reads the old tile back takes the 16 x 16 x 32 body (cheaper MFMA shape, old tile staged through
+// LDS) when its contraction is at least this long, else the 32 x 32 x 16 body (old tile loaded straight into the
+// accumulators, 128-byte row pieces, overlapped with the first operand loads).  Measured per tile: the staged
+// read-back costs about 17 us more, the cheaper shape gains about 2.9 us per 1024 rows of contraction (config 3,
+// 8192 rows: dW launch 0.818 -> 0.798 ms; the MLP's weight gradients, 4096 rows: 1.184 -> 1.229).
+constexpr int kStagedReadBackMinRows = 6144;
+
 // The same tile on the 16x16x32 instruction.  Its main loop is a few percent faster, its fp32 pass slower (a
 // store covers 4 rows x 64 bytes instead of 2 rows x 128): it serves the passes that only store (the first
-// row block of a dW pass, or the only one), dw_tile the passes that also read dW back.
+// row block of a dW pass, or the only one) and the read-back passes with a long contraction (see above).
 __device__ __forceinline__ void dw_tile16(
     const __bf16* __restrict__ G, int ldg, int g_cols, const __bf16* __restrict__ Hc, int ldh, int rows, int d, int V,
     int vt, int jt, int accumulate, float scale, float* __restrict__ dW, int ldw, char* smem) {
@@ -721,19 +728,38 @@ __device__ __forceinline__ void dw_tile16(
   f32x4 acc[kTA16][kTB16];
   zero_acc<kTA16, kTB16>(acc);
   if (accumulate) {
+    // The old tile comes in through LDS, which is free before the main loop: whole 1 KB rows, one wave instruction
+    // each (in the accumulator layout a lane's elements are 64-byte row pieces), two halves of 128 rows.  Half h
+    // holds tile rows 128 w + 64 h + (0..63) of both wave rows w.  The 16-byte pieces of LDS row p are XORed by
+    // 4 * ((p / 4) % 4), so that the four lane quarters of a read (rows 4 apart) fall on four bank groups.
+    typedef __attribute__((address_space(3))) const float* lds_f32_ptr;
+    const uint32_t lds0 = lds_addr_of(smem);
+    const int g = lane >> 4, c = lane & 15;
 #pragma unroll
-    for (int u = 0; u < kTB16; ++u)
-      if (col_ok[u]) {
+    for (int h = 0; h < 2; ++h) {
 #pragma unroll
-        for (int t = 0; t < kTA16; ++t)
-#pragma unroll
-          for (int r = 0; r < 4; ++r)
-            acc[t][u][r] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(out, lane_off[u] + row_off(t, r), 0, kNonTemporal));
+      for (int i = 0; i < 16; ++i) {
+        const int p = 16 * wave + i;
+        const uint32_t tile_row = 128 * (p >> 6) + 64 * h + (p & 63);
+        const uint32_t piece = (uint32_t)lane ^ (4u * ((p >> 2) & 3));
+        dma16(out, j0 + 4 * (int)piece < d ? (tile_row * (uint32_t)ldw + (uint32_t)j0 + 4u * piece) * 4u : kOutOfRange,
+              lds0 + p * 1024);
       }
+      wait_vmcnt<0>();
+      __syncthreads();
 #pragma unroll
-    for (int t = 0; t < kTA16; ++t)
+      for (int tt = 0; tt < kTA16 / 2; ++tt)
 #pragma unroll
-      for (int u = 0; u < kTB16; ++u) asm volatile("" : "+v"(acc[t][u]));
+        for (int u = 0; u < kTB16; ++u)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int p = 64 * wa + 16 * tt + 4 * g + r;
+            const int piece = (16 * wb + 4 * u + (c >> 2)) ^ (4 * g);
+            acc[kTA16 / 2 * h + tt][u][r] = *(lds_f32_ptr)(uintptr_t)(lds0 + p * 1024 + piece * 16 + (c & 3) * 4);
+          }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      __syncthreads();
+    }
   }
   PanelKS16<Tile16, kTile, kTA16> pa;
   PanelKS16<Tile16, kTile, kTB16> pb;
@@ -765,6 +791,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dw(
   if (!xcd_tile_2d(n_vt, n_jt, &vt, &jt)) return;
   const float scale = last ? gamma_of(n_valid, grad_loss) : 1.0f;
   if (kStoreOnly) dw_tile16(G, ldg, ldg, Hc, d, rows, d, V, vt, jt, 0, scale, dW, d, smem);
+  else if (rows >= kStagedReadBackMinRows) dw_tile16(G, ldg, ldg, Hc, d, rows, d, V, vt, jt, 1, scale, dW, d, smem);
   else dw_tile(G, ldg, ldg, Hc, d, rows, d, V, vt, jt, 1, scale, dW, d, smem);
 }
 
@@ -790,6 +817,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dh_dw(
   if (!xcd_tile_2d(n_vt, n_jt, &vt, &jt, (int)blockIdx.x - dh_grid)) return;
   const float scale = dw_last ? gamma_of(n_valid, grad_loss) : 1.0f;
   if (kStoreOnly) dw_tile16(G, ldg, ldg, Hc, d, rows, d, V, vt, jt, 0, scale, dW, d, smem);
+  else if (rows >= kStagedReadBackMinRows) dw_tile16(G, ldg, ldg, Hc, d, rows, d, V, vt, jt, 1, scale, dW, d, smem);
   else dw_tile(G, ldg, ldg, Hc, d, rows, d, V, vt, jt, 1, scale, dW, d, smem);
 }
 

@@ -386,6 +386,10 @@ def schedule():
     (1800, 136, 2900, 12, 3, 4),    # three row blocks: dW stored, accumulated, accumulated and scaled
     (600, 64, 70000, 1, 1, 2),      # wide windows, V not a multiple of 8
     (9000, 64, 600, 3, 2, 2),       # two row blocks of more than 4096 rows each (long contraction in the dW pass that reads dW back)
+    (13001, 72, 601, 2, 2, 2),      # row blocks of 6656 and 6345 rows: the read-back pass is long enough for the tile body
+                                    # that stages the old dW tile through LDS; ragged d (72) and a last vocabulary tile of 89 rows
+    (20000, 264, 520, 2, 3, 2),     # three such row blocks (6912, 6912, 6176): stored, staged + accumulated, staged + scaled;
+                                    # second column tile 8 wide, last vocabulary tile 8 rows
 ])
 @pytest.mark.parametrize("fused", [False, True])
 def test_block_schedule_matches_oracle(schedule, S, d, V, M, blocks, windows, fused):
