@@ -108,7 +108,7 @@ void choose_schedule(Plan* p, int forced) {
     if (n_win != MST_FORCE_WINDOWS) continue;
 #endif
     const int64_t ldg_w = (int64_t)win_tiles * kTile;
-    const int64_t per_row = ldg_w * 2 + d * 4;
+    const int64_t per_row = ldg_w * 2 + (int64_t)n_jt * kTile * 4;   // dlogits + fp32 dH sums (whole column tiles)
     if (p->b_total < 256 + (size_t)per_row * kTile) continue;
     int64_t R = (int64_t)((p->b_total - 256) / (size_t)per_row) / kTile * kTile;
     const int64_t S_up = (S + kTile - 1) / kTile * kTile;

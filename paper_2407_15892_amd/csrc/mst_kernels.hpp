@@ -464,9 +464,13 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dlogits(
 //   kDhSplit  one launch covers the whole contraction: n_split > 1 writes fp32 partials for k_bwd_dh_reduce,
 //             n_split == 1 writes gamma * result as bf16 (the row-chunk schedule)
 //   kDhFirst / kDhAdd / kDhLast  the contraction arrives in several launches, one per vocabulary window
-//             (n_split must be 1): the first stores the fp32 sums into partial[rows_stride][d], the middle ones add
-//             to them, the last adds and writes gamma * total as bf16.  Launches run in order on one stream, so
-//             the summation order is fixed.
+//             (n_split must be 1): the first stores the fp32 sums into `partial`, the middle ones add to them, the
+//             last adds and writes gamma * total as bf16.  Launches run in order on one stream, so the summation
+//             order is fixed.  Nobody else reads these sums, so they are kept in accumulator order, not row-major:
+//             tile (st, jt) owns 256 KB at partial + (st * n_jt + jt) * 65536 floats, and in it the four registers
+//             of accumulator (t, u) of wave w, lane l sit at float ((w * 32 + t * 4 + u) * 64 + l) * 4 -- one 16-byte
+//             load or store per accumulator and lane, 1 KB contiguous per wave instruction, whole tiles always
+//             (no masks; the padding of ragged tiles is written and read back like the rest and never leaves).
 constexpr int kDhSplit = 0, kDhFirst = 1, kDhAdd = 2, kDhLast = 3;
 // The body is a device function (block = index of the workgroup within this kernel's tile space) so that a
 // launch can serve the dH and the dW tiles of a vocabulary window together.
@@ -512,18 +516,18 @@ __device__ __forceinline__ void dh_tile(
 
   f32x4 acc[kTA16][kTB16];
   zero_acc<kTA16, kTB16>(acc);
+  typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+  const __amdgpu_buffer_rsrc_t tile_sums =
+      make_rsrc_uniform(partial + ((size_t)st * n_jt + jt) * (size_t)(kTile * kTile), (uint32_t)(kTile * kTile * 4));
+  const uint32_t slot0 = (uint32_t)(wave * (kTA16 * kTB16) * 64 + lane) * 16u;      // this lane's slot of accumulator (0, 0)
   if (mode == kDhAdd || mode == kDhLast) {
     // the running sums of the earlier windows go straight into the accumulators (the loads fly while the first
     // operand panels arrive) and are tied off so that the compiler puts no wait for them into the main loop
 #pragma unroll
-    for (int u = 0; u < kTB16; ++u)
-      if (col_ok[u]) {
+    for (int t = 0; t < kTA16; ++t)
 #pragma unroll
-        for (int t = 0; t < kTA16; ++t)
-#pragma unroll
-          for (int r = 0; r < 4; ++r)
-            acc[t][u][r] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(sums, lane_off[u] + row_off(t, r), 0, 0));
-      }
+      for (int u = 0; u < kTB16; ++u)
+        acc[t][u] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(tile_sums, slot0 + (t * kTB16 + u) * 1024, 0, 0));
   }
   // The preloaded sums are tied off behind the first operand loads (see gemm_mainloop_pp), not in front of them --
   // on every path, also where nothing was preloaded: behind a condition the compiler would carry "loads pending"
@@ -542,15 +546,23 @@ __device__ __forceinline__ void dh_tile(
 
   const bool to_bf16 = mode == kDhLast || (mode == kDhSplit && n_split == 1);
   if (!to_bf16) {
+    if (mode == kDhSplit) {        // partials for k_bwd_dh_reduce: row-major
 #pragma unroll
-    for (int u = 0; u < kTB16; ++u)
-      if (col_ok[u]) {
+      for (int u = 0; u < kTB16; ++u)
+        if (col_ok[u]) {
 #pragma unroll
-        for (int t = 0; t < kTA16; ++t)
+          for (int t = 0; t < kTA16; ++t)
 #pragma unroll
-          for (int r = 0; r < 4; ++r)
-            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[t][u][r]), sums, lane_off[u] + row_off(t, r), 0, 0);
-      }
+            for (int r = 0; r < 4; ++r)
+              __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[t][u][r]), sums, lane_off[u] + row_off(t, r), 0, 0);
+        }
+    } else {                       // running sums for the next window: accumulator order
+#pragma unroll
+      for (int t = 0; t < kTA16; ++t)
+#pragma unroll
+        for (int u = 0; u < kTB16; ++u)
+          __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, acc[t][u]), tile_sums, slot0 + (t * kTB16 + u) * 1024, 0, 0);
+    }
     return;
   }
   // bf16 result: the lanes of a wave instruction hold 16 adjacent columns of 4 rows, 32 bytes per row; staged in

@@ -380,15 +380,15 @@ def schedule():
 
 
 @pytest.mark.parametrize("S,d,V,M,blocks,windows", [
-    (1024, 128, 3000, 8, 2, 3),     # two row blocks of 512 rows, three windows, ragged last window (V = 11.7 tiles)
-    (1000, 136, 2900, 4, 1, 3),     # one ragged row block, d not a multiple of 64
-    (1400, 72, 5000, 12, 2, 4),     # ragged second row block (768 + 632 rows)
-    (1800, 136, 2900, 12, 3, 4),    # three row blocks: dW stored, accumulated, accumulated and scaled
+    (1024, 128, 3000, 8, 2, 4),     # two row blocks of 512 rows, four windows of 768, ragged last window (V = 11.7 tiles)
+    (1000, 136, 2900, 4, 1, 4),     # one ragged row block, d not a multiple of 64
+    (1400, 72, 5000, 12, 2, 7),     # ragged second row block (768 + 632 rows), seven windows
+    (1800, 136, 2900, 12, 4, 3),    # four row blocks: dW stored, accumulated twice, accumulated and scaled
     (600, 64, 70000, 1, 1, 2),      # wide windows, V not a multiple of 8
-    (9000, 64, 600, 3, 2, 2),       # two row blocks of more than 4096 rows each (long contraction in the dW pass that reads dW back)
+    (9000, 64, 600, 2, 2, 2),       # two row blocks of more than 4096 rows each (long contraction in the dW pass that reads dW back)
     (13001, 72, 601, 2, 2, 2),      # row blocks of 6656 and 6345 rows: the read-back pass is long enough for the tile body
                                     # that stages the old dW tile through LDS; ragged d (72) and a last vocabulary tile of 89 rows
-    (20000, 264, 520, 2, 3, 2),     # three such row blocks (6912, 6912, 6176): stored, staged + accumulated, staged + scaled;
+    (26000, 264, 520, 2, 3, 2),     # three such row blocks (8704, 8704, 8592): stored, staged + accumulated, staged + scaled;
                                     # second column tile 8 wide, last vocabulary tile 8 rows
 ])
 @pytest.mark.parametrize("fused", [False, True])
