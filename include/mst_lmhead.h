@@ -50,7 +50,7 @@
  *   - The device must be a whole MI355X (256 compute units behind one HIP
  *     device); a partitioned device is refused with MST_ERR_NO_DEVICE because the
  *     tile maps are laid out for 8 XCDs of 32 compute units.
- *   - Requirements: d % 8 == 0; H, W, dH 16-byte aligned; dW, lse 4-byte
+ *   - Requirements: d % 8 == 0; H, W, dH, dW 16-byte aligned; lse 4-byte
  *     aligned; workspace 256-byte aligned; 1 <= M <= S; d < 2^22;
  *     V * d < 2^31; ceil(S/M) * (V rounded up to 8) < 2^30.
  *   - Arithmetic: bf16 operands, fp32 MFMA accumulation, fp32 log-sum-exp and

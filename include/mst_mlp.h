@@ -41,8 +41,8 @@
  *   - Return value: MST_OK (0) or a negative error code of mst_lmhead.h
  *     (MST_ERR_BAD_SHAPE also covers I).  Argument errors are found on the
  *     host before anything is launched.
- *   - Requirements: d % 8 == 0, I % 8 == 0; X, Wg, Wu, Wd, dO, O, dX 16-byte
- *     aligned; dWg, dWu, dWd 4-byte aligned; workspace 256-byte aligned;
+ *   - Requirements: d % 8 == 0, I % 8 == 0; X, Wg, Wu, Wd, dO, O, dX, dWg,
+ *     dWu, dWd 16-byte aligned; workspace 256-byte aligned;
  *     1 <= M <= S; d, I < 2^22; I * d < 2^31; ceil(S/M) * I < 2^30.
  *   - Arithmetic: bf16 operands, fp32 MFMA accumulation; silu, its derivative
  *     and the products in fp32 on the accumulators; A, dA, dG, dU rounded to

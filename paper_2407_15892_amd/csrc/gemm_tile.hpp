@@ -6,9 +6,8 @@
 // 256 x 64 bf16 are brought from global memory straight into LDS (buffer loads with the LDS bit, 16 bytes
 // per lane, no register staging), three stages deep for the A operand and two for the B operand (all 160 KB
 // of LDS), and consumed by MFMA instructions.  The wave grid is 2 (A side) x 4 (B side): a wave accumulates
-// 128 x 64 = 128 fp32 accumulator registers per lane.  This header holds the main loop and the panel classes
-// for v_mfma_f32_32x32x16_bf16 tiles (4 x 2 per wave, used by the weight-gradient passes); gemm_tile16.hpp
-// holds the panel classes for v_mfma_f32_16x16x32_bf16 tiles (8 x 4 per wave, used by everything else).
+// 128 x 64 = 128 fp32 accumulator registers per lane.  This header holds the main loop; gemm_tile16.hpp holds
+// the tile configuration and the panel classes for v_mfma_f32_16x16x32_bf16 tiles (8 x 4 per wave).
 //
 // The two halves of the workgroup (waves 0-3 and 4-7, one wave of each half on every SIMD) run half a step
 // apart: while one half reads its fragments of a stage out of LDS and issues the global loads of later
@@ -36,22 +35,6 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr uint32_t kOutOfRange = 0xFFFFFF00u;
 
-template <int WA_, int WB_, int TA_, int TB_, int BK_, int NS_>
-struct Cfg {
-  static constexpr int WA = WA_, WB = WB_, TA = TA_, TB = TB_, BK = BK_, NS = NS_;
-  static constexpr int kWaves = WA * WB, kThreads = 64 * kWaves;
-  static constexpr int EA = 32 * TA * WA, EB = 32 * TB * WB;
-  static constexpr int kPanelA = EA * BK * 2, kPanelB = EB * BK * 2;
-  // LDS stages per operand: the B operand has NS, the A operand one more (its loads are issued one K step earlier)
-  static constexpr int NSA = NS + 1, NSB = NS;
-  static constexpr int kLds = NSA * kPanelA + NSB * kPanelB;
-  static constexpr int kKK = BK / 16;            // MFMA k sub-steps per stage
-  typedef f32x16 Acc;                            // accumulator of one 32 x 32 MFMA tile
-  __device__ __forceinline__ static Acc mma(bf16x8 a, bf16x8 b, Acc c) {
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
-  }
-};
-
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
 }
@@ -76,74 +59,6 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_
 __device__ __forceinline__ uint32_t lds_addr_of(const void* p) {
   return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
 }
-template <bool kPermute> __device__ __forceinline__ int a_row_of_mfma_row(int i) {
-  if (!kPermute) return i;
-  return 16 * ((i >> 2) & 1) + 4 * (i >> 3) + (i & 3);
-}
-
-// K-strided panel [BK k][EXT index].  kPermute (A side only): MFMA row m of a 32-wide tile reads index
-// a_row_of_mfma_row(m), so that a lane's 16 accumulator registers hold 16 consecutive indices.  The
-// permutation keeps groups of 4 consecutive indices together, which is the granule one lane hands to the
-// transposing read, so it is applied in the read addresses and the panel in LDS stays in memory order.
-template <class C, int EXT, int TILES, bool kPermute = false>
-struct PanelKS {
-  static constexpr int BK = C::BK;
-  static constexpr int RB = EXT * 2;
-  static constexpr int CPR = EXT / 8;
-  static constexpr int RPS = 1024 / RB;         // k rows per slot
-  static constexpr int NSLOT = BK / RPS;
-  static constexpr int SPW = NSLOT / C::kWaves;
-  static_assert(NSLOT % C::kWaves == 0, "slots must divide over waves");
-  static constexpr int kBytes = BK * RB;
-  // XOR swizzle of the 16-byte chunk index by the k row.  The two lane quarters served in one clock read the
-  // same 4 k rows, 32 bytes (2 chunks) apart in memory order: with a step of 4 chunks per row the 8 pieces of
-  // 32 bytes fall on 8 different bank groups (a step of 2 made row r of one quarter meet row r + 1 of the other).
-  static constexpr uint32_t kSwz = kPermute ? 2 : 4;
-  __amdgpu_buffer_rsrc_t rsrc;
-  uint32_t voff[SPW];
-  uint32_t ok_mask, ld_bytes, slot0;
-  uint32_t rd[TILES];
-
-  __device__ __forceinline__ void init(const void* base, uint32_t ld_elems, uint32_t k_rows, uint32_t cols_valid,
-                                       int wave, int lane, int wave_side_index) {
-    ld_bytes = ld_elems * 2;
-    const uint32_t last_cols = cols_valid < ld_elems ? cols_valid : ld_elems;
-    rsrc = make_rsrc(base, (k_rows - 1) * ld_bytes + last_cols * 2);
-    slot0 = wave * SPW;
-    ok_mask = 0;
-#pragma unroll
-    for (int i = 0; i < SPW; ++i) {
-      const uint32_t krow = RPS * (slot0 + i) + lane / CPR;
-      const uint32_t chunk = (lane % CPR) ^ (kSwz * (krow & 3));
-      voff[i] = krow * ld_bytes + chunk * 16;
-      ok_mask |= ((chunk * 8) < cols_valid ? 1u : 0u) << i;
-    }
-    const int g = lane >> 4, i16 = lane & 15;
-#pragma unroll
-    for (int t = 0; t < TILES; ++t) {
-      const int m0 = 16 * (g & 1) + 4 * (i16 & 3);          // first of the 4 MFMA rows this lane's piece feeds
-      const int col = wave_side_index * (32 * TILES) + 32 * t + a_row_of_mfma_row<kPermute>(m0);
-      const int krow = 8 * (g >> 1) + (i16 >> 2);
-      rd[t] = krow * RB + (((col >> 3) ^ (kSwz * (i16 >> 2))) * 16) + (col & 7) * 2;
-    }
-  }
-  __device__ __forceinline__ void issue_one(int i, uint32_t panel_lds, uint32_t k0) const {
-    dma16(rsrc, ((ok_mask >> i) & 1u) ? voff[i] + k0 * ld_bytes : kOutOfRange, panel_lds + (slot0 + i) * 1024);
-  }
-  __device__ __forceinline__ void issue(uint32_t panel_lds, uint32_t k0) const {
-#pragma unroll
-    for (int i = 0; i < SPW; ++i) issue_one(i, panel_lds, k0);
-  }
-  __device__ __forceinline__ bf16x8 frag(const char* panel, int t, int kk) const {
-    typedef __attribute__((address_space(3))) i16x4* lds_i16x4_ptr;
-    const char* p = panel + rd[t] + kk * (16 * RB);
-    i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)(p));
-    i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)(p + 4 * RB));
-    i16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_bit_cast(bf16x8, v);
-  }
-};
-
 // Ping-pong main loop for 8 waves (WA == 2): waves 0-3 (group 0) and 4-7 (group 1) alternate between a
 // memory phase (global->LDS loads of later stages + all fragment reads of the current stage) and a compute
 // phase (all MFMAs of the stage), one workgroup barrier per phase, group 1 running one phase behind group 0.

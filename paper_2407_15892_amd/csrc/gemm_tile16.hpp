@@ -1,18 +1,19 @@
-// The same block-tile main loop on v_mfma_f32_16x16x32_bf16 tiles.
+// Tile configuration and operand panels of the block-tile main loop (gemm_tile.hpp) for
+// v_mfma_f32_16x16x32_bf16 tiles.
 //
 // On random operands a register-resident loop of the 16 x 16 x 32 instruction sustains about 15 % more flop
 // per second than the 32 x 32 x 16 one on this power-limited chip, and inside the GEMMs of this library the
-// difference is 4-6 %.  The block tile, the wave grid (2 x 4, wave tile 128 x 64), the LDS stages and the
-// ping-pong loop are those of gemm_tile.hpp; what changes is the fragment and accumulator layout:
+// difference was 4-6 % when both were built; every kernel uses 16 x 16 x 32.  Block tile 256 x 256, wave grid
+// 2 x 4, wave tile 128 x 64; fragment and accumulator layout:
 //
 //   A fragment  lane l holds row (l % 16) of a 16-row tile, k = 8 * (l / 16) .. + 7 of a 32-wide k sub-step
 //   B fragment  lane l holds column (l % 16), same k
 //   accumulator register r of lane l is D[4 * (l / 16) + r][l % 16]               (4 registers per tile)
 //
-// so a wave tile is 8 x 4 MFMA tiles (128 accumulator registers, as before), a K step of 64 is two k
-// sub-steps, and a lane quarter g = l / 16 owns accumulator rows 4g..4g+3 of every tile.  With the A-side
-// permutation (LDS row 16 t + 4 g + r of a 128-row block holds source row 32 g + 4 t + r) the 8 tiles x 4
-// registers of a lane cover 32 consecutive A indices: 64-byte bf16 stores per lane.
+// so a wave tile is 8 x 4 MFMA tiles (128 accumulator registers), a K step of 64 is two k sub-steps, and a
+// lane quarter g = l / 16 owns accumulator rows 4g..4g+3 of every tile.  With the A-side permutation (LDS row
+// 16 t + 4 g + r of a 128-row block holds source row 32 g + 4 t + r) the 8 tiles x 4 registers of a lane
+// cover 32 consecutive A indices: 64-byte bf16 stores per lane.
 #pragma once
 #include "gemm_tile.hpp"
 

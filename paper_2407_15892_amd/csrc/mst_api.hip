@@ -449,7 +449,7 @@ mst_status mst_lmhead_ce_bwd(const void* H, const void* W, const int32_t* labels
   const size_t need = !lse ? p.b_total_max : (!n_valid ? p.b_lse : p.b_total);
   if (!workspace || workspace_bytes < need) return MST_ERR_WORKSPACE;
   if (misaligned(H, 16) || misaligned(W, 16) || misaligned(dH, 16) || misaligned(workspace, 256) ||
-      misaligned(lse, 4) || misaligned(dW, 4) || misaligned(labels, 4) || misaligned(n_valid, 8))
+      misaligned(lse, 4) || misaligned(dW, 16) || misaligned(labels, 4) || misaligned(n_valid, 8))
     return MST_ERR_ALIGNMENT;
   if ((s = prepare_device()) != MST_OK) return s;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);

@@ -21,22 +21,19 @@
 
 namespace mst {
 
-// tile configurations: 2 x 4 waves, wave tile 128 x 64, K step 64, LDS stages 3 (A) + 2 (B).
-//   Tile16: 8 x 4 tiles of v_mfma_f32_16x16x32_bf16 per wave -- the three logits-shaped GEMMs
-//   Tile:   4 x 2 tiles of v_mfma_f32_32x32x16_bf16 per wave -- the dW pass, whose fp32 read-modify-write of the
-//           output tile is better served by 32 lanes (128 bytes) per row than by 16
+// tile configuration: 2 x 4 waves, wave tile 128 x 64, K step 64, LDS stages 3 (A) + 2 (B), 8 x 4 tiles of
+// v_mfma_f32_16x16x32_bf16 per wave (on random operands this power-limited chip sustains more flop/s with it than
+// with v_mfma_f32_32x32x16_bf16, whose only advantage -- 128-byte instead of 64-byte row pieces in fp32 epilogues --
+// went away when the fp32 intermediates moved to accumulator order)
 typedef Cfg16<2, 4, 8, 4, 64, 2> Tile16;
 constexpr int kTA16 = Tile16::TA, kTB16 = Tile16::TB;
-static_assert(Tile16::EA == 256 && Tile16::EB == 256 && Tile16::kLds == 5 * 32768, "same block tile, same LDS");
-typedef Cfg<2, 4, 4, 2, 64, 2> Tile;
 // same wave grid, half as wide on the B side: 256 x 128 block tile, wave tile 128 x 32
 typedef Cfg16<2, 4, 8, 2, 64, 2> Tile16HalfB;
-constexpr int kTile = 256;             // Tile::EA == Tile::EB
-constexpr int kBK = Tile::BK;
-constexpr int kThreads = Tile::kThreads;
-constexpr int kLdsBytes = Tile::kLds;
-constexpr int kTA = Tile::TA, kTB = Tile::TB;
-static_assert(Tile::EA == kTile && Tile::EB == kTile, "square 256 x 256 block tile");
+constexpr int kTile = 256;             // Tile16::EA == Tile16::EB
+constexpr int kBK = Tile16::BK;
+constexpr int kThreads = Tile16::kThreads;
+constexpr int kLdsBytes = Tile16::kLds;
+static_assert(Tile16::EA == kTile && Tile16::EB == kTile && kLdsBytes == 5 * 32768, "square 256 x 256 block tile, all of LDS");
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -155,6 +152,7 @@ __global__ __launch_bounds__(1024) void k_label_scan(const int* __restrict__ lab
 
 // register-resident MFMA loop: the matrix-core rate the chip sustains without any data movement
 __global__ __launch_bounds__(kThreads) void k_mfma_probe(float* sink, int iters, float scale) {
+  constexpr int kTA = 4, kTB = 2;          // 4 x 2 tiles of 32 x 32: 128 accumulator registers, as in the GEMM kernels
   f32x16 acc[kTA][kTB];
   zero_acc<kTA, kTB>(acc);
   bf16x8 a[8], b[8];
@@ -637,90 +635,17 @@ __global__ __launch_bounds__(256) void k_bwd_dh_reduce(const float* __restrict__
 // ---------------------------------------------------------------------------
 // G: [rows][ldg], columns [0, g_cols) readable (v < V of them used); Hc: [rows][ldh], columns [0, d) used;
 // dW: [V][ldw], columns [0, d) written
+//
+// Between the passes over one dW tile (`accumulate`: an earlier pass has stored it; `more`: a later pass will add
+// to it) nobody else reads the tile, so a whole tile (256 rows and 256 columns inside the matrix) is kept in
+// accumulator order inside its own footprint: wave instruction (w, t, u) moves row 32 w + 4 t + u of the tile's 256
+// rows of 1 KB, lane l its bytes 16 l .. 16 l + 15 -- the four registers of accumulator (t, u).  One 16-byte load or
+// store per accumulator and lane, 1 KB contiguous per wave instruction, straight between memory and the
+// accumulators.  Only the last pass (more == 0) writes the matrix in row-major order.  Tiles on a ragged edge keep
+// row-major order throughout: 64-byte row pieces out, and in through LDS.
 __device__ __forceinline__ void dw_tile(
     const __bf16* __restrict__ G, int ldg, int g_cols, const __bf16* __restrict__ Hc, int ldh, int rows, int d, int V,
-    int vt, int jt, int accumulate, float scale, float* __restrict__ dW, int ldw, char* smem) {
-  const int v0 = vt * kTile, j0 = jt * kTile;
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int wa = wave >> 2, wb = wave & 3;
-
-  // The fp32 tile is read and written through a buffer descriptor that covers the tile's valid rows: one
-  // scalar-base instruction per element with a 32-bit offset, rows past V dropped by the hardware range
-  // check (loads of them return 0), columns past d masked per lane.  Both streams are non-temporal.
-  const int rows_valid = V - v0 < kTile ? V - v0 : kTile;
-  const __amdgpu_buffer_rsrc_t out = make_rsrc_uniform(dW + (size_t)v0 * ldw, (uint32_t)rows_valid * (uint32_t)ldw * 4u);
-  constexpr int kNonTemporal = 2;
-  uint32_t lane_off[kTB];
-  bool col_ok[kTB];
-#pragma unroll
-  for (int u = 0; u < kTB; ++u) {
-    const int j = j0 + wb * 64 + 32 * u + (lane & 31);
-    col_ok[u] = j < d;
-    lane_off[u] = ((uint32_t)(wa * 128 + 4 * (lane >> 5)) * (uint32_t)ldw + (uint32_t)j) * 4u;
-  }
-  // register r of accumulator tile t holds row 32 t + 8 (r / 4) + r % 4 (+ the lane part above)
-  auto row_off = [&](int t, int r) { return (uint32_t)(32 * t + 8 * (r >> 2) + (r & 3)) * (uint32_t)ldw * 4u; };
-
-  f32x16 acc[kTA][kTB];
-  zero_acc<kTA, kTB>(acc);
-  if (accumulate) {
-#pragma unroll
-    for (int u = 0; u < kTB; ++u)
-      if (col_ok[u]) {
-#pragma unroll
-        for (int t = 0; t < kTA; ++t)
-#pragma unroll
-          for (int r = 0; r < 16; ++r)
-            acc[t][u][r] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(out, lane_off[u] + row_off(t, r), 0, kNonTemporal));
-      }
-  }
-  // The compiler has to see these loads complete before the first MFMA: its own wait-count bookkeeping cannot see
-  // the loop's hand-placed waits, so it would otherwise wait for every outstanding load (the operand prefetches
-  // included) in front of the first MFMAs of every K step.  The tie-off sits behind the first operand loads.
-  auto tie_off = [&]() {
-    if (accumulate) {
-#pragma unroll
-      for (int t = 0; t < kTA; ++t)
-#pragma unroll
-        for (int u = 0; u < kTB; ++u) asm volatile("" : "+v"(acc[t][u]));
-    }
-  };
-  PanelKS<Tile, kTile, kTA> pa;
-  PanelKS<Tile, kTile, kTB> pb;
-  pa.init(G + v0, ldg, rows, g_cols - v0, wave, lane, wa);
-  pb.init(Hc + j0, ldh, rows, d - j0, wave, lane, wb);
-  gemm_mainloop_pp<Tile>(acc, pa, pb, smem, 0, rows, wa, tie_off);
-
-  // scaled in place first: a store whose data sits in a reused temporary would have to wait for older stores
-#pragma unroll
-  for (int t = 0; t < kTA; ++t)
-#pragma unroll
-    for (int u = 0; u < kTB; ++u) acc[t][u] *= scale;
-#pragma unroll
-  for (int u = 0; u < kTB; ++u)
-    if (col_ok[u]) {
-#pragma unroll
-      for (int t = 0; t < kTA; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-          __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[t][u][r]), out, lane_off[u] + row_off(t, r), 0, kNonTemporal);
-    }
-}
-
-// A dW pass that reads the old tile back takes the 16 x 16 x 32 body (cheaper MFMA shape, old tile staged through
-// LDS) when its contraction is at least this long, else the 32 x 32 x 16 body (old tile loaded straight into the
-// accumulators, 128-byte row pieces, overlapped with the first operand loads).  Measured per tile: the staged
-// read-back costs about 17 us more, the cheaper shape gains about 2.9 us per 1024 rows of contraction (config 3,
-// 8192 rows: dW launch 0.818 -> 0.798 ms; the MLP's weight gradients, 4096 rows: 1.184 -> 1.229).
-constexpr int kStagedReadBackMinRows = 6144;
-
-// The same tile on the 16x16x32 instruction.  Its main loop is a few percent faster, its fp32 pass slower (a
-// store covers 4 rows x 64 bytes instead of 2 rows x 128): it serves the passes that only store (the first
-// row block of a dW pass, or the only one) and the read-back passes with a long contraction (see above).
-__device__ __forceinline__ void dw_tile16(
-    const __bf16* __restrict__ G, int ldg, int g_cols, const __bf16* __restrict__ Hc, int ldh, int rows, int d, int V,
-    int vt, int jt, int accumulate, float scale, float* __restrict__ dW, int ldw, char* smem) {
+    int vt, int jt, int accumulate, int more, float scale, float* __restrict__ dW, int ldw, char* smem) {
   const int v0 = vt * kTile, j0 = jt * kTile;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -737,9 +662,19 @@ __device__ __forceinline__ void dw_tile16(
     lane_off[u] = ((uint32_t)(wa * 128 + 4 * (lane >> 4)) * (uint32_t)ldw + (uint32_t)j) * 4u;
   }
   auto row_off = [&](int t, int r) { return (uint32_t)(16 * t + r) * (uint32_t)ldw * 4u; };
+  typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+  const bool whole = rows_valid == kTile && j0 + kTile <= d;
+  const uint32_t slot0 = ((uint32_t)(wave * (kTA16 * kTB16)) * (uint32_t)ldw + (uint32_t)j0) * 4u + (uint32_t)lane * 16u;
+  auto slot = [&](int t, int u) { return slot0 + (uint32_t)(t * kTB16 + u) * (uint32_t)ldw * 4u; };
   f32x4 acc[kTA16][kTB16];
   zero_acc<kTA16, kTB16>(acc);
-  if (accumulate) {
+  if (accumulate && whole) {
+#pragma unroll
+    for (int t = 0; t < kTA16; ++t)
+#pragma unroll
+      for (int u = 0; u < kTB16; ++u)
+        acc[t][u] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(out, slot(t, u), 0, kNonTemporal));
+  } else if (accumulate) {
     // The old tile comes in through LDS, which is free before the main loop: whole 1 KB rows, one wave instruction
     // each (in the accumulator layout a lane's elements are 64-byte row pieces), two halves of 128 rows.  Half h
     // holds tile rows 128 w + 64 h + (0..63) of both wave rows w.  The 16-byte pieces of LDS row p are XORed by
@@ -773,15 +708,30 @@ __device__ __forceinline__ void dw_tile16(
       __syncthreads();
     }
   }
+  // the directly loaded tile is tied off behind the first operand loads (see gemm_mainloop_pp), on every path
+  auto tie_off = [&]() {
+#pragma unroll
+    for (int t = 0; t < kTA16; ++t)
+#pragma unroll
+      for (int u = 0; u < kTB16; ++u) asm volatile("" : "+v"(acc[t][u]));
+  };
   PanelKS16<Tile16, kTile, kTA16> pa;
   PanelKS16<Tile16, kTile, kTB16> pb;
   pa.init(G + v0, ldg, rows, g_cols - v0, wave, lane, wa);
   pb.init(Hc + j0, ldh, rows, d - j0, wave, lane, wb);
-  gemm_mainloop_pp<Tile16>(acc, pa, pb, smem, 0, rows, wa);
+  gemm_mainloop_pp<Tile16>(acc, pa, pb, smem, 0, rows, wa, tie_off);
 #pragma unroll
   for (int t = 0; t < kTA16; ++t)
 #pragma unroll
     for (int u = 0; u < kTB16; ++u) acc[t][u] *= scale;
+  if (more && whole) {
+#pragma unroll
+    for (int t = 0; t < kTA16; ++t)
+#pragma unroll
+      for (int u = 0; u < kTB16; ++u)
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, acc[t][u]), out, slot(t, u), 0, kNonTemporal);
+    return;
+  }
 #pragma unroll
   for (int u = 0; u < kTB16; ++u)
     if (col_ok[u]) {
@@ -802,9 +752,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dw(
   int vt, jt;
   if (!xcd_tile_2d(n_vt, n_jt, &vt, &jt)) return;
   const float scale = last ? gamma_of(n_valid, grad_loss) : 1.0f;
-  if (kStoreOnly) dw_tile16(G, ldg, ldg, Hc, d, rows, d, V, vt, jt, 0, scale, dW, d, smem);
-  else if (rows >= kStagedReadBackMinRows) dw_tile16(G, ldg, ldg, Hc, d, rows, d, V, vt, jt, 1, scale, dW, d, smem);
-  else dw_tile(G, ldg, ldg, Hc, d, rows, d, V, vt, jt, 1, scale, dW, d, smem);
+  dw_tile(G, ldg, ldg, Hc, d, rows, d, V, vt, jt, kStoreOnly ? 0 : 1, last ? 0 : 1, scale, dW, d, smem);
 }
 
 // dH and dW of one (row block, vocabulary window) from one launch: both read the same dlogits block and
@@ -828,9 +776,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_gemm_dh_dw(
   int vt, jt;
   if (!xcd_tile_2d(n_vt, n_jt, &vt, &jt, (int)blockIdx.x - dh_grid)) return;
   const float scale = dw_last ? gamma_of(n_valid, grad_loss) : 1.0f;
-  if (kStoreOnly) dw_tile16(G, ldg, ldg, Hc, d, rows, d, V, vt, jt, 0, scale, dW, d, smem);
-  else if (rows >= kStagedReadBackMinRows) dw_tile16(G, ldg, ldg, Hc, d, rows, d, V, vt, jt, 1, scale, dW, d, smem);
-  else dw_tile(G, ldg, ldg, Hc, d, rows, d, V, vt, jt, 1, scale, dW, d, smem);
+  dw_tile(G, ldg, ldg, Hc, d, rows, d, V, vt, jt, kStoreOnly ? 0 : 1, dw_last ? 0 : 1, scale, dW, d, smem);
 }
 
 }  // namespace mst

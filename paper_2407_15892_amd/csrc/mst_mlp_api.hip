@@ -193,7 +193,7 @@ mst_status mst_mlp_bwd(const void* X, const void* Wg, const void* Wu, const void
   if (!X || !Wg || !Wu || !Wd || !dO || !dX || !dWg || !dWu || !dWd) return MST_ERR_NULL_POINTER;
   if (!workspace || workspace_bytes < 3 * p.slot) return MST_ERR_WORKSPACE;
   if (misaligned(X, 16) || misaligned(Wg, 16) || misaligned(Wu, 16) || misaligned(Wd, 16) || misaligned(dO, 16) ||
-      misaligned(dX, 16) || misaligned(dWg, 4) || misaligned(dWu, 4) || misaligned(dWd, 4) || misaligned(workspace, 256))
+      misaligned(dX, 16) || misaligned(dWg, 16) || misaligned(dWu, 16) || misaligned(dWd, 16) || misaligned(workspace, 256))
     return MST_ERR_ALIGNMENT;
   if ((s = prepare_device()) != MST_OK) return s;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
@@ -236,7 +236,7 @@ mst_status mst_mlp_bwd(const void* X, const void* Wg, const void* Wu, const void
       ps.p[1] = dw_problem(bufU, dI, Xc, dd, dd, dI, dWu);     // dWu [I][d] (+)= dU^T X
       ps.p[2] = dw_problem(dOc, dd, bufA, dI, dI, dd, dWd);    // dWd [d][I] (+)= dO^T A
       hipLaunchKernelGGL(acc ? k_mlp_dw3<false> : k_mlp_dw3<true>, dim3(ps.p[0].grid + ps.p[1].grid + ps.p[2].grid),
-                         dim3(kThreads), kLdsBytes, st, ps, rows);
+                         dim3(kThreads), kLdsBytes, st, ps, rows, i + 1 < p.n_chunks ? 1 : 0);
     }
   }
   return check_launch();
