@@ -201,34 +201,35 @@ def main_mlp(args) -> int:
     fwd_ms, bwd_ms = e[0].elapsed_time(e[1]), e[1].elapsed_time(e[2])
 
     timing = not args.no_kernel_timing
-    mst.mst_mlp_profile_enable(timing)
+    mst.mst_mlp_profile_enable(max(1, args.kernel_timing_every) if timing else 0)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         fwd(); bwd()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    kern = mst.mst_mlp_profile_collect() if timing else {}
-    mst.mst_mlp_profile_enable(False)
+    kern = mst.mst_mlp_profile_collect() if timing else {}   # kind -> (ms of the timed launches, timed launches, all launches)
+    mst.mst_mlp_profile_enable(0)
 
     ms_per_step = dt * 1e3 / args.steps
     f_exec = 22.0 * S * d * I          # forward 6, recomputation 4, dA 2, dX 4, weight gradients 6
     tflops = f_exec / (ms_per_step * 1e-3) / 1e12
     roofline, kernels = None, {}
     if kern:
-        for k, (ms, n) in kern.items():
+        for k, (ms, n, issued) in kern.items():
             if n:
-                fl = MLP_FLOP_UNITS[k] * S * d * I / (n / args.steps)
-                kernels[k] = {"launches": n, "avg_ms": ms / n, "total_ms_per_step": ms / args.steps,
-                              "tflops": fl / (ms / n * 1e-3) / 1e12}
-        dom = max(MLP_KINDS, key=lambda k: kern[k][0])
-        ms, n = kern[dom]
-        fl = MLP_FLOP_UNITS[dom] * S * d * I / (n / args.steps)
+                fl = MLP_FLOP_UNITS[k] * S * d * I / (issued / args.steps)
+                kernels[k] = {"launches": issued, "timed_launches": n, "avg_ms": ms / n,
+                              "total_ms_per_step": ms / n * issued / args.steps, "tflops": fl / (ms / n * 1e-3) / 1e12}
+        dom = max(MLP_KINDS, key=lambda k: kernels.get(k, {}).get("total_ms_per_step", 0.0))
+        ms, n, issued = kern[dom]
+        fl = MLP_FLOP_UNITS[dom] * S * d * I / (issued / args.steps)
         achieved = fl / (ms / n * 1e-3) / 1e12
         roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
                     "traffic": pmc_traffic_bytes("mlp", args.config, "-", dom),
-                    "flop_per_launch": fl, "avg_launch_ms": ms / n, "launches_per_step": n / args.steps}
+                    "flop_per_launch": fl, "avg_launch_ms": ms / n, "launches_per_step": issued / args.steps,
+                    "timed_launches": n}
     out = {
         "metric": "MsT-MLP fwd+bwd TFLOP/s (22*S*d*I executed flop incl. recomputation)",
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -271,6 +272,10 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="do not bracket kernels with events inside the timed region")
+    ap.add_argument("--kernel-timing-every", type=int, default=3,
+                    help="bracket every n-th launch of each kernel kind with events inside the timed region (default 3: "
+                         "the launches of a kind repeat with period 8 or 32, so a stride of 3 visits every position; events "
+                         "on every launch cost 0.4-0.7 %% of the step)")
     ap.add_argument("--library-gemm", action="store_true",
                     help="LM-head path: after the timed region also time the path's three contractions as plain library "
                          "GEMMs (torch.matmul, bf16) on the same H and W and a materialised softmax: a yardstick for what "
@@ -355,7 +360,7 @@ def main() -> int:
     fwd_ms, bwd_ms = e[0].elapsed_time(e[1]), e[1].elapsed_time(e[2])
 
     timing = not args.no_kernel_timing
-    mst.mst_profile_enable(timing)
+    mst.mst_profile_enable(max(1, args.kernel_timing_every) if timing else 0)
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -365,8 +370,8 @@ def main() -> int:
         marks[i + 1].record(stream)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    kern = mst.mst_profile_collect() if timing else {}
-    mst.mst_profile_enable(False)
+    kern = mst.mst_profile_collect() if timing else {}      # kind -> (ms of the timed launches, timed launches, all launches)
+    mst.mst_profile_enable(0)
     per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
 
     ms_per_step = dt * 1e3 / args.steps
@@ -377,31 +382,32 @@ def main() -> int:
     roofline = None
     kernels = {}
     if kern:
-        for k, (ms, n) in kern.items():
+        for k, (ms, n, issued) in kern.items():
             if n:
-                kernels[k] = {"launches": n, "avg_ms": ms / n, "total_ms_per_step": ms / args.steps}
+                kernels[k] = {"launches": issued, "timed_launches": n, "avg_ms": ms / n,
+                              "total_ms_per_step": ms / n * issued / args.steps}
         # a GEMM kind executes GEMM_KINDS[kind] * S*d*V flop per step in total, split over its launches of that step
         def flop_per_launch(kind):
-            return GEMM_KINDS[kind] * S * d * V / (kern[kind][1] / args.steps)
-        dom = max(GEMM_KINDS, key=lambda k: kern.get(k, (0.0, 0))[0])
-        ms, n = kern[dom]
+            return GEMM_KINDS[kind] * S * d * V / (kern[kind][2] / args.steps)
+        dom = max(GEMM_KINDS, key=lambda k: kernels.get(k, {}).get("total_ms_per_step", 0.0))
+        ms, n, issued = kern[dom]
         achieved = flop_per_launch(dom) / (ms / n * 1e-3) / 1e12
         traffic = None if (args.m or args.rows) else pmc_traffic_bytes("lmhead", args.config, sched["schedule"], dom)
         roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
                     "flop_per_launch": flop_per_launch(dom), "avg_launch_ms": ms / n,
-                    "launches_per_step": n / args.steps}
+                    "launches_per_step": issued / args.steps, "timed_launches": n}
         if dom == "bwd_gemm_dw":
             # this kernel also moves dW through HBM: every row block writes it, every block after the first reads it
             # first; dlogits is read once, H once per vocabulary window
-            passes = n / args.steps
+            passes = issued / args.steps
             n_rb, n_win = sched["row_blocks"], sched["windows"]
             alg_bytes = ((2 * n_rb - 1) * 4.0 * V * d + 2.0 * S * V + 2.0 * S * d * n_win) / passes
             roofline["hbm_side"] = {"algorithmic_bytes_per_launch": alg_bytes,
                                     "achieved_GBs": alg_bytes / (ms / n * 1e-3) / 1e9, "peak_GBs": PEAK_HBM_GBS,
                                     "frac": alg_bytes / (ms / n * 1e-3) / 1e9 / PEAK_HBM_GBS}
         for k in GEMM_KINDS:
-            ms_k, n_k = kern.get(k, (0.0, 0))
+            ms_k, n_k, _ = kern.get(k, (0.0, 0, 0))
             if n_k:
                 kernels[k]["tflops"] = flop_per_launch(k) / (ms_k / n_k * 1e-3) / 1e12
 
@@ -415,8 +421,8 @@ def main() -> int:
                     0.5 * (per_step[len(per_step) // 2 - 1] + per_step[len(per_step) // 2]),
                     "min": per_step[0], "max": per_step[-1], "n": len(per_step),
                     "what": "individual timed steps, events between steps on the launch stream"},
-        "kernel_timing": ("per-launch HIP events recorded by the library inside the timed region" if timing
-                          else "off"),
+        "kernel_timing": (f"HIP events recorded by the library inside the timed region around every "
+                          f"{max(1, args.kernel_timing_every)}-th launch of each kernel kind" if timing else "off"),
         "target": {"frac_of_bf16_peak": 0.60, "ms_per_step_at_target": f_exec / (0.60 * PEAK_BF16_TFLOPS * 1e12) * 1e3,
                    "gap_ms": ms_per_step - f_exec / (0.60 * PEAK_BF16_TFLOPS * 1e12) * 1e3},
         "config": {"workload": f"config {cfg.index} {cfg.name}: S={S} d={d} V={V} M={M} (C={cfg.C}), "

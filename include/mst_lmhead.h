@@ -264,11 +264,16 @@ int32_t mst_tile_of_workgroup(int32_t n_slow, int32_t n_fast, int32_t order, int
 mst_status mst_mfma_probe(int32_t blocks, int32_t iters, float scale, float* sink, void* stream);
 
 /*
- * Per-kernel timing (host).  When enabled, every kernel launch of the two calls
- * above is bracketed by HIP events on the caller's stream.  mst_profile_collect
- * waits for the recorded events, adds the elapsed milliseconds and launch
- * counts per kernel kind into the caller's arrays (each of length
- * MST_PROFILE_KINDS, indexed by the enum below) and clears the record.
+ * Per-kernel timing (host).  mst_profile_enable(every): 0 switches it off; n >= 1
+ * brackets every n-th launch of each kernel kind of the two calls above (the
+ * first, the n + 1st, ...) with HIP events on the caller's stream -- the events
+ * themselves take a few microseconds each on the stream, so a caller that times
+ * a whole step around them may prefer n > 1.  mst_profile_collect waits for the
+ * recorded events, adds per kernel kind the elapsed milliseconds and the number
+ * of launches they cover (their quotient is the average launch time) and, if
+ * issued_per_kind is not NULL, the number of all launches of that kind while
+ * timing was on, into the caller's arrays (each of length MST_PROFILE_KINDS,
+ * indexed by the enum below), and clears the record.
  */
 enum {
   MST_K_LABEL_SCAN = 0,  /* N_valid, label range check                         */
@@ -282,8 +287,8 @@ enum {
   MST_K_BWD_GEMM_DH_DW,  /* both of the above for one block, from one launch    */
   MST_PROFILE_KINDS
 };
-mst_status mst_profile_enable(int enable);
-mst_status mst_profile_collect(double* ms_per_kind, int64_t* launches_per_kind);
+mst_status mst_profile_enable(int every);
+mst_status mst_profile_collect(double* ms_per_kind, int64_t* launches_per_kind, int64_t* issued_per_kind);
 const char* mst_profile_kind_name(int kind);
 
 #ifdef __cplusplus

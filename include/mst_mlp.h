@@ -106,9 +106,11 @@ mst_status mst_mlp_bwd(const void* X, const void* Wg, const void* Wu, const void
                        void* dX, float* dWg, float* dWu, float* dWd, void* stream);
 
 /*
- * Per-kernel timing (host), as in mst_lmhead.h: when enabled every launch of
- * the two calls above is bracketed by HIP events on the caller's stream;
- * collect adds elapsed milliseconds and launch counts per kind (arrays of
+ * Per-kernel timing (host), as in mst_lmhead.h: mst_mlp_profile_enable(every)
+ * brackets every `every`-th launch of each kernel kind of the two calls above
+ * with HIP events on the caller's stream (0 = off); collect adds, per kind, the
+ * elapsed milliseconds, the number of launches they cover and (if the pointer
+ * is not NULL) the number of all launches while timing was on (arrays of
  * length MST_MLP_PROFILE_KINDS) and clears the record.
  */
 enum {
@@ -120,8 +122,8 @@ enum {
   MST_MLP_K_DW,           /* dWg += dG_i^T X_i, dWu += dU_i^T X_i, dWd += dO_i^T A_i  */
   MST_MLP_PROFILE_KINDS
 };
-mst_status mst_mlp_profile_enable(int enable);
-mst_status mst_mlp_profile_collect(double* ms_per_kind, int64_t* launches_per_kind);
+mst_status mst_mlp_profile_enable(int every);
+mst_status mst_mlp_profile_collect(double* ms_per_kind, int64_t* launches_per_kind, int64_t* issued_per_kind);
 const char* mst_mlp_profile_kind_name(int kind);
 
 #ifdef __cplusplus

@@ -78,7 +78,7 @@ def load_library() -> ctypes.CDLL:
     lib.mst_profile_enable.restype = c.c_int
     lib.mst_profile_enable.argtypes = [c.c_int]
     lib.mst_profile_collect.restype = c.c_int
-    lib.mst_profile_collect.argtypes = [c.POINTER(c.c_double), c.POINTER(c.c_int64)]
+    lib.mst_profile_collect.argtypes = [c.POINTER(c.c_double), c.POINTER(c.c_int64), c.POINTER(c.c_int64)]
     lib.mst_profile_kind_name.restype = c.c_char_p
     lib.mst_profile_kind_name.argtypes = [c.c_int]
     _lib = lib
@@ -196,14 +196,16 @@ def mst_bwd_schedule_info(S: int, d: int, V: int, M: int, schedule: Optional[int
     return dict(zip(keys, (int(x) for x in info)))
 
 
-def mst_profile_enable(enable: bool) -> None:
-    _check(load_library().mst_profile_enable(1 if enable else 0))
+def mst_profile_enable(every) -> None:
+    """0 / False: off; n >= 1 (True = 1): bracket every n-th launch of each kernel kind with events."""
+    _check(load_library().mst_profile_enable(int(every)))
 
 
 def mst_profile_collect():
-    """{kernel kind name: (milliseconds, launches)} since the last collect."""
+    """{kernel kind name: (milliseconds of the timed launches, timed launches, all launches)} since the last collect."""
     ms = (ctypes.c_double * PROFILE_KINDS)()
     n = (ctypes.c_int64 * PROFILE_KINDS)()
-    _check(load_library().mst_profile_collect(ms, n))
+    issued = (ctypes.c_int64 * PROFILE_KINDS)()
+    _check(load_library().mst_profile_collect(ms, n, issued))
     lib = load_library()
-    return {lib.mst_profile_kind_name(i).decode(): (float(ms[i]), int(n[i])) for i in range(PROFILE_KINDS)}
+    return {lib.mst_profile_kind_name(i).decode(): (float(ms[i]), int(n[i]), int(issued[i])) for i in range(PROFILE_KINDS)}

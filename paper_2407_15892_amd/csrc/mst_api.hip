@@ -623,13 +623,13 @@ int32_t mst_tile_grid(int32_t n_slow, int32_t n_fast) {
   return xcd_grid_2d(n_slow, n_fast);
 }
 
-mst_status mst_profile_enable(int enable) {
-  g_prof.enable(enable != 0);
+mst_status mst_profile_enable(int every) {
+  g_prof.enable(every);
   return MST_OK;
 }
 
-mst_status mst_profile_collect(double* ms_per_kind, int64_t* launches_per_kind) {
-  return g_prof.collect(MST_PROFILE_KINDS, ms_per_kind, launches_per_kind) ? MST_OK : MST_ERR_LAUNCH;
+mst_status mst_profile_collect(double* ms_per_kind, int64_t* launches_per_kind, int64_t* issued_per_kind) {
+  return g_prof.collect(MST_PROFILE_KINDS, ms_per_kind, launches_per_kind, issued_per_kind) ? MST_OK : MST_ERR_LAUNCH;
 }
 
 const char* mst_profile_kind_name(int kind) {

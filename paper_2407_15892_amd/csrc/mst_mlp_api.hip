@@ -242,13 +242,13 @@ mst_status mst_mlp_bwd(const void* X, const void* Wg, const void* Wu, const void
   return check_launch();
 }
 
-mst_status mst_mlp_profile_enable(int enable) {
-  g_prof.enable(enable != 0);
+mst_status mst_mlp_profile_enable(int every) {
+  g_prof.enable(every);
   return MST_OK;
 }
 
-mst_status mst_mlp_profile_collect(double* ms_per_kind, int64_t* launches_per_kind) {
-  return g_prof.collect(MST_MLP_PROFILE_KINDS, ms_per_kind, launches_per_kind) ? MST_OK : MST_ERR_LAUNCH;
+mst_status mst_mlp_profile_collect(double* ms_per_kind, int64_t* launches_per_kind, int64_t* issued_per_kind) {
+  return g_prof.collect(MST_MLP_PROFILE_KINDS, ms_per_kind, launches_per_kind, issued_per_kind) ? MST_OK : MST_ERR_LAUNCH;
 }
 
 const char* mst_mlp_profile_kind_name(int kind) {

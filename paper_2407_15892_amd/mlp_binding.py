@@ -49,7 +49,7 @@ def load_mlp_library() -> ctypes.CDLL:
     lib.mst_mlp_profile_enable.restype = c.c_int
     lib.mst_mlp_profile_enable.argtypes = [c.c_int]
     lib.mst_mlp_profile_collect.restype = c.c_int
-    lib.mst_mlp_profile_collect.argtypes = [c.POINTER(c.c_double), c.POINTER(c.c_int64)]
+    lib.mst_mlp_profile_collect.argtypes = [c.POINTER(c.c_double), c.POINTER(c.c_int64), c.POINTER(c.c_int64)]
     lib.mst_mlp_profile_kind_name.restype = c.c_char_p
     lib.mst_mlp_profile_kind_name.argtypes = [c.c_int]
     _lib = lib
@@ -101,14 +101,16 @@ def mst_mlp_bwd(X, Wg, Wu, Wd, dO, M: int, workspace, dX, dWg, dWu, dWd, stream=
         _ptr(dX), _ptr(dWg), _ptr(dWu), _ptr(dWd), _stream_handle(stream)))
 
 
-def mst_mlp_profile_enable(enable: bool) -> None:
-    _check(load_mlp_library().mst_mlp_profile_enable(1 if enable else 0))
+def mst_mlp_profile_enable(every) -> None:
+    """0 / False: off; n >= 1 (True = 1): bracket every n-th launch of each kernel kind with events."""
+    _check(load_mlp_library().mst_mlp_profile_enable(int(every)))
 
 
 def mst_mlp_profile_collect():
-    """{kind name: (total ms, launches)} since the last collect."""
+    """{kind name: (ms of the timed launches, timed launches, all launches)} since the last collect."""
     ms = (ctypes.c_double * MLP_PROFILE_KINDS)()
     n = (ctypes.c_int64 * MLP_PROFILE_KINDS)()
-    _check(load_mlp_library().mst_mlp_profile_collect(ms, n))
+    issued = (ctypes.c_int64 * MLP_PROFILE_KINDS)()
+    _check(load_mlp_library().mst_mlp_profile_collect(ms, n, issued))
     lib = load_mlp_library()
-    return {lib.mst_mlp_profile_kind_name(i).decode(): (float(ms[i]), int(n[i])) for i in range(MLP_PROFILE_KINDS)}
+    return {lib.mst_mlp_profile_kind_name(i).decode(): (float(ms[i]), int(n[i]), int(issued[i])) for i in range(MLP_PROFILE_KINDS)}

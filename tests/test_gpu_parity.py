@@ -612,3 +612,31 @@ def test_two_callers_on_two_streams_do_not_disturb_each_other():
         torch.cuda.synchronize()
         for got, want in zip(snapshot(oa) + snapshot(ob), want_a + want_b):
             assert torch.equal(got, want), f"replay {rep}: outputs differ between concurrent and serial calls"
+
+
+def test_kernel_timing_covers_every_nth_launch_of_each_kind():
+    """mst_profile_enable(n) brackets the first, the n + 1st, ... launch of each kernel kind; collect returns the time of
+    those launches, how many they were, and how many launches of the kind there were in all."""
+    import torch
+    import paper_2407_15892_amd as mst
+    DeviceRun, _ = _harness()
+    inp = mi.make_inputs(mi.custom_config(1500, 256, 3000, 6, index=640, w_std=0.2, ignore_frac=0.1, label_dist="zipf"))
+    run = DeviceRun(inp)
+    counts = {}
+    for every in (1, 3):
+        mst.mst_profile_enable(every)
+        try:
+            for _ in range(2):
+                run.forward()
+                run.backward()
+            torch.cuda.synchronize()
+            got = mst.mst_profile_collect()
+        finally:
+            mst.mst_profile_enable(0)
+        counts[every] = got
+        for kind, (ms, timed, issued) in got.items():
+            assert timed == -(-issued // every), (kind, every, timed, issued)
+            assert (ms > 0.0) == (timed > 0), (kind, ms, timed)
+    assert {k: v[2] for k, v in counts[1].items()} == {k: v[2] for k, v in counts[3].items()}
+    assert counts[1]["fwd_gemm_lse"][2] == 2 and counts[1]["bwd_gemm_dlogits"][2] >= 2
+    assert all(v == (0.0, 0, 0) for v in mst.mst_profile_collect().values()), "collect clears the record"
