@@ -222,8 +222,8 @@ mst_status mst_lmhead_ce_bwd(const void* H, const void* W, const int32_t* labels
  *   MST_BWD_SCHEDULE_BLOCKS_FUSED  the block order with the dH and the dW GEMM of each (row block, window)
  *                            in one launch: their tile spaces then share one partly filled last round of
  *                            workgroups instead of leaving one each (same arithmetic as BLOCKS, bit for bit).
- *   MST_BWD_SCHEDULE_AUTO    (default) whichever a host-side cost model (rounds of workgroups plus fp32
- *                            gradient traffic) ranks faster for the shape.
+ *   MST_BWD_SCHEDULE_AUTO    (default) PAIRS or BLOCKS_FUSED, whichever a host-side cost model (rounds of
+ *                            workgroups plus fp32 gradient traffic) ranks faster for the shape.
  * mst_set_bwd_schedule: host; the override belongs to the CALLING THREAD (thread-local, AUTO in every new
  * thread) and takes effect at that thread's next backward call, so one caller's setting never changes the
  * summation order of another thread's call; MST_ERR_BAD_SHAPE for an unknown value.

@@ -71,7 +71,6 @@ struct Plan {
 // gradient traffic at a nominal bandwidth; it only has to rank the candidates.
 constexpr double kUsPerKStep = 1.5;      // one 256 x 256 x 64 block-tile step with one workgroup per CU
 constexpr double kRmwBytesPerUs = 4.0e6; // fp32 read-modify-write streams next to a running GEMM
-constexpr double kFuseWaste = 0.0125;     // idle share of separate dH and dW launches from which one launch serves both
 double rounds_us(int64_t tiles, int64_t k) {
   return (double)((tiles + kNumCu - 1) / kNumCu) * (double)((k + kBK - 1) / kBK) * kUsPerKStep;
 }
@@ -116,7 +115,7 @@ void choose_schedule(Plan* p, int forced) {
     const int n_rb = (int)((S + R - 1) / R);
     R = ((S + n_rb - 1) / n_rb + kTile - 1) / kTile * kTile;
     if (R * ldg_w >= (int64_t(1) << 30) || R * d >= (int64_t(1) << 30)) continue;   // 32-bit offsets inside a block
-    double t = 0.0, sep_us = 0.0, work_us = 0.0;
+    double t = 0.0;
     for (int rb = 0; rb < n_rb; ++rb) {
       const int64_t rows = (S - rb * R) < R ? (S - rb * R) : R;
       const int64_t n_st = (rows + kTile - 1) / kTile;
@@ -126,20 +125,15 @@ void choose_schedule(Plan* p, int forced) {
         t += rounds_us(n_st * tiles_w, d);                                                 // dlogits
         t += (double)((w > 0 ? 4 : 0) + (w + 1 < n_win ? 4 : 2)) * (double)(rows * d) / kRmwBytesPerUs;
         t += (double)((rb > 0 ? 8 : 4) * cols * d) / kRmwBytesPerUs;
-        const double dh_dw = rounds_us(n_st * n_jt, cols) + rounds_us(tiles_w * n_jt, rows);  // two launches
-        t += dh_dw;
-        sep_us += dh_dw;
-        work_us += ((double)(n_st * n_jt) * (double)((cols + kBK - 1) / kBK) +
-                    (double)(tiles_w * n_jt) * (double)((rows + kBK - 1) / kBK)) / kNumCu * kUsPerKStep;
+        t += rounds_us(n_st * n_jt, cols) + rounds_us(tiles_w * n_jt, rows);               // dH, dW
       }
     }
     // One launch for the dH and the dW tiles of a block: a partly filled last round of dH workgroups is topped up
-    // with dW tiles, and one launch boundary per block goes away.  Measured: no difference where both tile counts
-    // fill whole rounds anyway (config 2: 512 and 1008 tiles), -1.5 to -2 % of the step where they do not (Gemma
-    // shape: 896 dH tiles = 3.5 rounds; config 5: 496).  It is used when the two separate launches would leave at
-    // least kFuseWaste of their CU time idle; the block shapes are ranked without it.
-    const bool fuse = forced == MST_BWD_SCHEDULE_BLOCKS_FUSED ||
-                      (forced == MST_BWD_SCHEDULE_AUTO && sep_us - work_us >= kFuseWaste * sep_us);
+    // with dW tiles, and one launch boundary per block goes away.  Measured: -0.25 to -0.4 % of the step where both
+    // tile counts fill whole rounds anyway (configs 2 and 3: 512 and 1008 tiles), -1.5 to -2 % where they do not
+    // (Gemma shape: 896 dH tiles = 3.5 rounds; config 5: 496).  The automatic choice always takes it; the block
+    // shapes are ranked as separate launches.
+    const bool fuse = forced == MST_BWD_SCHEDULE_BLOCKS_FUSED || forced == MST_BWD_SCHEDULE_AUTO;
     const double t_pick = t;
     if (!p->blk_use || t_pick < best) {
       best = t_pick;

@@ -158,8 +158,8 @@ def test_backward_schedule_choice_and_block_shapes(mst):
                 assert auto["schedule"] == mst.BWD_SCHEDULE_PAIRS, (cfg.name, auto)
         # large vocabulary, short chunks: blocks; tiny problems: pairs
         mst.mst_set_bwd_schedule(mst.BWD_SCHEDULE_AUTO)
-        assert mst.mst_bwd_schedule_info(8192, 4096, 128256, 8)["schedule"] == mst.BWD_SCHEDULE_BLOCKS
-        # 64 x 14 dH tiles leave half a round of workgroups idle: dH and dW share a launch
+        # where blocks win, the automatic choice lets dH and dW share a launch
+        assert mst.mst_bwd_schedule_info(8192, 4096, 128256, 8)["schedule"] == mst.BWD_SCHEDULE_BLOCKS_FUSED
         assert mst.mst_bwd_schedule_info(16384, 3584, 256000, 16)["schedule"] == mst.BWD_SCHEDULE_BLOCKS_FUSED
         assert mst.mst_bwd_schedule_info(512, 256, 4096, 4)["schedule"] == mst.BWD_SCHEDULE_PAIRS
         with pytest.raises(mst.MstError):
@@ -227,16 +227,17 @@ def test_schedule_override_is_per_thread_and_the_pure_query_ignores_it(mst):
 
         def other():
             seen["fresh_thread"] = mst.mst_bwd_schedule_info(*shape)["schedule"]
-            mst.mst_set_bwd_schedule(mst.BWD_SCHEDULE_BLOCKS_FUSED)
+            mst.mst_set_bwd_schedule(mst.BWD_SCHEDULE_BLOCKS)
             seen["after_own_set"] = mst.mst_bwd_schedule_info(*shape)["schedule"]
 
         th = threading.Thread(target=other)
         th.start()
         th.join()
-        assert seen["fresh_thread"] == mst.BWD_SCHEDULE_BLOCKS          # AUTO's choice for this shape
-        assert seen["after_own_set"] == mst.BWD_SCHEDULE_BLOCKS_FUSED
+        assert seen["fresh_thread"] == mst.BWD_SCHEDULE_BLOCKS_FUSED    # AUTO's choice for this shape
+        assert seen["after_own_set"] == mst.BWD_SCHEDULE_BLOCKS
         assert mst.mst_bwd_schedule_info(*shape)["schedule"] == mst.BWD_SCHEDULE_PAIRS   # this thread's is untouched
-        for forced, want in ((mst.BWD_SCHEDULE_AUTO, mst.BWD_SCHEDULE_BLOCKS), (mst.BWD_SCHEDULE_PAIRS, mst.BWD_SCHEDULE_PAIRS),
+        for forced, want in ((mst.BWD_SCHEDULE_AUTO, mst.BWD_SCHEDULE_BLOCKS_FUSED), (mst.BWD_SCHEDULE_PAIRS, mst.BWD_SCHEDULE_PAIRS),
+                             (mst.BWD_SCHEDULE_BLOCKS, mst.BWD_SCHEDULE_BLOCKS),
                              (mst.BWD_SCHEDULE_BLOCKS_FUSED, mst.BWD_SCHEDULE_BLOCKS_FUSED)):
             assert mst.mst_bwd_schedule_info(*shape, schedule=forced)["schedule"] == want
         assert mst.mst_bwd_schedule_info(*shape)["schedule"] == mst.BWD_SCHEDULE_PAIRS
