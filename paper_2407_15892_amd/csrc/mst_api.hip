@@ -264,8 +264,10 @@ mst_status prepare_device() {
 }
 
 // forward pass over all chunks: writes lse (if non-null) and nll (if non-null)
+// `queue`: eight zeroed ints for the persistent forward launches (nullptr: one workgroup per tile)
 mst_status run_forward_chunks(const Plan& p, const __bf16* H, const __bf16* W, const int32_t* labels,
-                              int ignore_index, char* ws, float* lse, float* nll, hipStream_t st) {
+                              int ignore_index, char* ws, float* lse, float* nll, hipStream_t st, int* queue = nullptr) {
+  int queue_base = 0;
   float* tgt = reinterpret_cast<float*>(ws + p.f_tgt);
   float2* part = reinterpret_cast<float2*>(ws + p.f_part);
   const size_t stride = (size_t)p.fwd_group_rows;
@@ -277,9 +279,12 @@ mst_status run_forward_chunks(const Plan& p, const __bf16* H, const __bf16* W, c
       // shorter than a 256-row tile costs no idle tile rows, and every row's result is bit-identical for every M.
       const int n_st = (int)((g_rows + kTile - 1) / kTile);
       Scope sc(st, MST_K_FWD_GEMM_LSE);
-      hipLaunchKernelGGL(k_fwd_gemm_lse, dim3(xcd_grid_2d(p.n_vt, n_st)), dim3(kThreads), kLdsBytes, st,
+      const int tiles = xcd_grid_2d(p.n_vt, n_st);
+      const int grid = queue && tiles > kNumCu ? kNumCu : tiles;
+      hipLaunchKernelGGL(k_fwd_gemm_lse, dim3(grid), dim3(kThreads), kLdsBytes, st,
                          H + g0 * p.d, W, labels + g0, (int)g_rows, (int)p.d, (int)p.V, n_st, p.n_vt,
-                         part, stride, tgt);
+                         part, stride, tgt, queue, queue_base);
+      queue_base += tiles / kNumXcd + grid;
     }
     {
       Scope sc(st, MST_K_LSE_FINALIZE);
@@ -310,7 +315,7 @@ mst_status enqueue_forward(const Plan& p, const void* H, const void* W, const in
     hipLaunchKernelGGL(k_label_scan, dim3(1), dim3(1024), 0, st, labels, (long long)p.S, (int)p.V, ignore_index, ctl);
   }
   const mst_status s = run_forward_chunks(p, static_cast<const __bf16*>(H), static_cast<const __bf16*>(W), labels,
-                                          ignore_index, ws, lse, nll, st);
+                                          ignore_index, ws, lse, nll, st, ctl->queue);
   if (s != MST_OK) return s;
   {
     Scope sc(st, MST_K_LOSS_REDUCE);

@@ -46,7 +46,8 @@ struct Control {
   int bad_labels;       // rows whose label is outside [0, V) and not the ignore value
   int pad0;
   long long n_valid_checked;   // n_valid, or -1 if bad_labels > 0: what a caller (or the backward pass) is handed
-  int pad[58];
+  int queue[8];         // per-XCD tile queues of the persistent forward launch (see TileFeed); zeroed by the label scan
+  int pad[50];
 };
 static_assert(sizeof(Control) == 256, "control block is one 256-byte line");
 
@@ -118,7 +119,83 @@ __device__ __forceinline__ bool xcd_tile_2d(int n_slow, int n_fast, int* slow, i
 __device__ __forceinline__ bool xcd_tile_2d_fast_major(int n_slow, int n_fast, int* slow, int* fast) {
   return xcd_tile_of_block<kXcdRectSlow, kXcdRectFast, kXcdRectFast>((int)blockIdx.x, n_slow, n_fast, slow, fast);
 }
-inline int xcd_grid_2d(int n_slow, int n_fast) { return kNumXcd * ((n_slow + kNumXcd - 1) / kNumXcd) * n_fast; }
+__host__ __device__ inline int xcd_grid_2d(int n_slow, int n_fast) { return kNumXcd * ((n_slow + kNumXcd - 1) / kNumXcd) * n_fast; }
+
+// Persistent workgroups that pull their tiles from per-XCD queues instead of owning one tile each.
+//
+// A launch of `grid` tiles in the maps above gives XCD x the workgroup indices x, x + 8, x + 16, ...: a list of
+// per_xcd = grid / 8 entries that its 32 resident workgroups take in order.  Here the launch has one workgroup per
+// compute unit, and workgroup b (on XCD b % 8, as the hardware deals them out) takes the next entry of its XCD's
+// list with an atomic add on queue[b % 8] -- the same order, so the rectangles of tiles that share operand panels
+// in an XCD's L2 are the same -- and, when that list is used up, goes on to the lists of the other XCDs: an XCD
+// that runs faster than the others (they differ by several per cent) takes over work of the slower ones, and the
+// launch ends with all compute units busy instead of with the slowest XCD.  Nobody waits for anybody: a workgroup
+// leaves when it has found all 8 lists used up.
+//
+// The counters are not reset between launches.  Every workgroup fails exactly once on every list, so a launch
+// leaves each counter at its old value + per_xcd + number of workgroups, which the host adds up into `base` for the
+// next launch on the same counters.  Thread 0 fetches; the index reaches the other threads through one LDS word in
+// the third A stage.  The fetch for the tile after this one is issued at the start of a tile and collected behind
+// the first operand loads of its main loop.
+//
+// Only the forward launch works this way.  It runs 250 rounds of tiles at the benchmark shape, so a difference of a
+// few per cent between XCDs adds up to several whole tiles (forward pass -2.3 %, same-box A/B); the backward launches
+// run 2 to 8 rounds, the difference never reaches one tile, and the queue bought nothing there (dlogits -0.2 %,
+// dH + dW 0).
+
+// The lane index, opaque to the compiler.  In a persistent kernel everything a tile body derives from the lane index
+// alone (panel offsets, output offsets) is invariant over the loop over tiles; hoisted out of it, those values would
+// have to live through the main loop, whose accumulators and fragments leave no registers free, and be spilled -- and
+// each reload (a vector-memory operation) would wait for the operand loads issued before it.  Read through this
+// function inside the loop they are recomputed per tile instead, which costs nothing next to a tile.
+__device__ __forceinline__ int lane_index_per_tile() {
+  int lane = (int)(threadIdx.x & 63);
+  asm volatile("" : "+v"(lane));
+  return lane;
+}
+
+constexpr int kFeedWordOffset = 2 * 32768;
+struct TileFeed {
+  int* queue;
+  int base, per_xcd, x, visited;
+  int pending;          // wave 0: the index fetched for the tile after the current one (uniform, lives in a scalar register)
+  int raw;              // thread 0: the atomic's result on its way back
+  char* smem;
+  __device__ __forceinline__ void init(int* q, int base_, int per_xcd_, char* smem_) {
+    queue = q; base = base_; per_xcd = per_xcd_; smem = smem_;
+    x = (int)(blockIdx.x % kNumXcd); visited = 0; pending = 0; raw = 0;
+    issue();
+    resolve();
+  }
+  // Thread 0 asks for the next entry of the current list.  Called at the start of a tile; resolve() is called behind
+  // the main loop's first operand loads, where the wave waits for memory anyway, and moves the answer into a scalar
+  // register (a vector register kept across the tile would be spilled, and the spill would wait for the answer at
+  // once).  Only wave 0 takes part.
+  __device__ __forceinline__ void issue() {
+    if (threadIdx.x == 0) raw = atomicAdd(queue + x, 1);        // nothing may touch the result before resolve()
+  }
+  __device__ __forceinline__ void resolve() {
+    if (__builtin_amdgcn_readfirstlane(threadIdx.x >> 6) == 0) pending = __builtin_amdgcn_readfirstlane(raw) - base;
+  }
+  // index of the next tile in the launch's static map, or -1 when every list is used up; all threads call it
+  __device__ __forceinline__ int next() {
+    int* word = reinterpret_cast<int*>(smem + kFeedWordOffset);
+    __syncthreads();                         // the previous tile's epilogue may still be reading LDS
+    if (threadIdx.x == 0) {
+      int t = pending;
+      while (t >= per_xcd) {
+        if (++visited == kNumXcd) { t = -1; break; }
+        x = (x + 1) % kNumXcd;
+        t = atomicAdd(queue + x, 1) - base;
+      }
+      *word = t < 0 ? -1 : t * kNumXcd + x;
+    }
+    __syncthreads();
+    const int block = __builtin_amdgcn_readfirstlane(*word);
+    __syncthreads();                         // a tile body may write this part of LDS before its first barrier
+    return block;
+  }
+};
 
 // ---------------------------------------------------------------------------
 // label scan: N_valid and range check.  One workgroup, integer sums only.
@@ -148,6 +225,7 @@ __global__ __launch_bounds__(1024) void k_label_scan(const int* __restrict__ lab
     ctl->bad_labels = tb;
     ctl->n_valid_checked = tb > 0 ? -1 : tv;
   }
+  if (threadIdx.x < kNumXcd) ctl->queue[threadIdx.x] = 0;
 }
 
 // register-resident MFMA loop: the matrix-core rate the chip sustains without any data movement
@@ -202,14 +280,21 @@ __global__ __launch_bounds__(256) void k_shift_labels(const int* __restrict__ in
 __global__ __launch_bounds__(kThreads) void k_fwd_gemm_lse(
     const __bf16* __restrict__ Hc, const __bf16* __restrict__ W, const int* __restrict__ labels_c,
     int rows, int d, int V, int n_st, int n_vt, float2* __restrict__ part, size_t part_stride,
-    float* __restrict__ tgt) {
+    float* __restrict__ tgt, int* __restrict__ queue, int queue_base) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  int vt, st;                                        // an XCD's resident workgroups: 4 vocabulary x 8 row tiles
-  if (!xcd_tile_2d(n_vt, n_st, &vt, &st)) return;
-  const int v0 = vt * kTile, s0 = st * kTile;
-  const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wa = wave >> 2, wb = wave & 3;
+  TileFeed feed;
+  if (queue) feed.init(queue, queue_base, xcd_grid_2d(n_vt, n_st) / kNumXcd, smem);
+  for (int block = queue ? feed.next() : (int)blockIdx.x; block >= 0; block = queue ? feed.next() : -1) {
+  int vt, st;                                        // an XCD's resident workgroups: 4 vocabulary x 8 row tiles
+  if (!xcd_tile_2d(n_vt, n_st, &vt, &st, block)) {   // padding entry of the map
+    if (queue) { feed.issue(); feed.resolve(); }
+    continue;
+  }
+  if (queue) feed.issue();
+  const int lane = lane_index_per_tile();
+  const int v0 = vt * kTile, s0 = st * kTile;
 
   f32x4 acc[kTA16][kTB16];
   zero_acc<kTA16, kTB16>(acc);
@@ -217,7 +302,7 @@ __global__ __launch_bounds__(kThreads) void k_fwd_gemm_lse(
   PanelKC16<Tile16, kTile, kTB16, false> pb;
   pa.init(W + (size_t)v0 * d, d, V - v0, d, wave, lane, wa);
   pb.init(Hc + (size_t)s0 * d, d, rows - s0, d, wave, lane, wb);
-  gemm_mainloop_pp<Tile16>(acc, pa, pb, smem, 0, d, wa);
+  gemm_mainloop_pp<Tile16>(acc, pa, pb, smem, 0, d, wa, [&]() { if (queue) feed.resolve(); });
 
   // a lane (quarter g, column c) holds, for each of its 4 rows s, the 32 consecutive vocabulary entries
   // va + 4 t + r (t = 0..7, r = 0..3)
@@ -291,6 +376,7 @@ __global__ __launch_bounds__(kThreads) void k_fwd_gemm_lse(
       const int s_local = s0 + wb * 64 + 16 * u + lane;
       if (s_local < rows) part[(size_t)vt * part_stride + s_local] = make_float2(mm, l);
     }
+  }
   }
 }
 
