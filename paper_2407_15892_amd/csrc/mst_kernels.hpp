@@ -727,8 +727,8 @@ __global__ __launch_bounds__(256) void k_bwd_dh_reduce(const float* __restrict__
 // accumulator order inside its own footprint: wave instruction (w, t, u) moves row 32 w + 4 t + u of the tile's 256
 // rows of 1 KB, lane l its bytes 16 l .. 16 l + 15 -- the four registers of accumulator (t, u).  One 16-byte load or
 // store per accumulator and lane, 1 KB contiguous per wave instruction, straight between memory and the
-// accumulators.  Only the last pass (more == 0) writes the matrix in row-major order.  Tiles on a ragged edge keep
-// row-major order throughout: 64-byte row pieces out, and in through LDS.
+// accumulators.  Only the last pass (more == 0) writes the matrix in row-major order, through LDS as whole 1 KB rows.
+// Tiles on a ragged edge keep row-major order throughout: 64-byte row pieces out, and in through LDS.
 __device__ __forceinline__ void dw_tile(
     const __bf16* __restrict__ G, int ldg, int g_cols, const __bf16* __restrict__ Hc, int ldh, int rows, int d, int V,
     int vt, int jt, int accumulate, int more, float scale, float* __restrict__ dW, int ldw, char* smem) {
@@ -816,6 +816,38 @@ __device__ __forceinline__ void dw_tile(
 #pragma unroll
       for (int u = 0; u < kTB16; ++u)
         __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, acc[t][u]), out, slot(t, u), 0, kNonTemporal);
+    return;
+  }
+  if (whole) {
+    // row-major result of a whole tile: through LDS (free after the main loop), out as whole 1 KB rows, 16 bytes per
+    // lane; the direct stores below are 64-byte row pieces, half cache lines
+    typedef __attribute__((address_space(3))) float* lds_f32_w;
+    typedef __attribute__((address_space(3))) const u32x4* lds_u4_r;
+    const uint32_t lds0 = lds_addr_of(smem);
+    const int g = lane >> 4, c = lane & 15;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      if (h) __syncthreads();
+#pragma unroll
+      for (int tt = 0; tt < kTA16 / 2; ++tt)
+#pragma unroll
+        for (int u = 0; u < kTB16; ++u)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int p = 64 * wa + 16 * tt + 4 * g + r;
+            const int piece = (16 * wb + 4 * u + (c >> 2)) ^ (4 * g);
+            *(lds_f32_w)(uintptr_t)(lds0 + p * 1024 + piece * 16 + (c & 3) * 4) = acc[kTA16 / 2 * h + tt][u][r];
+          }
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int p = 16 * wave + i;
+        const uint32_t tile_row = 128 * (p >> 6) + 64 * h + (p & 63);
+        const uint32_t piece = (uint32_t)lane ^ (4u * ((p >> 2) & 3));
+        const u32x4 v = *(lds_u4_r)(uintptr_t)(lds0 + p * 1024 + lane * 16);
+        __builtin_amdgcn_raw_buffer_store_b128(v, out, (tile_row * (uint32_t)ldw + (uint32_t)j0 + 4u * piece) * 4u, 0, kNonTemporal);
+      }
+    }
     return;
   }
 #pragma unroll
