@@ -733,25 +733,17 @@ __device__ __forceinline__ void dw_tile(
     const __bf16* __restrict__ G, int ldg, int g_cols, const __bf16* __restrict__ Hc, int ldh, int rows, int d, int V,
     int vt, int jt, int accumulate, int more, float scale, float* __restrict__ dW, int ldw, char* smem) {
   const int v0 = vt * kTile, j0 = jt * kTile;
-  const int lane = threadIdx.x & 63;
+  int lane = lane_index_per_tile();       // read once more behind the main loop: nothing derived from it lives through it
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wa = wave >> 2, wb = wave & 3;
   const int rows_valid = V - v0 < kTile ? V - v0 : kTile;
   const __amdgpu_buffer_rsrc_t out = make_rsrc_uniform(dW + (size_t)v0 * ldw, (uint32_t)rows_valid * (uint32_t)ldw * 4u);
   constexpr int kNonTemporal = 2;
-  uint32_t lane_off[kTB16];
-  bool col_ok[kTB16];
-#pragma unroll
-  for (int u = 0; u < kTB16; ++u) {
-    const int j = j0 + wb * 64 + 16 * u + (lane & 15);
-    col_ok[u] = j < d;
-    lane_off[u] = ((uint32_t)(wa * 128 + 4 * (lane >> 4)) * (uint32_t)ldw + (uint32_t)j) * 4u;
-  }
-  auto row_off = [&](int t, int r) { return (uint32_t)(16 * t + r) * (uint32_t)ldw * 4u; };
   typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
   const bool whole = rows_valid == kTile && j0 + kTile <= d;
-  const uint32_t slot0 = ((uint32_t)(wave * (kTA16 * kTB16)) * (uint32_t)ldw + (uint32_t)j0) * 4u + (uint32_t)lane * 16u;
-  auto slot = [&](int t, int u) { return slot0 + (uint32_t)(t * kTB16 + u) * (uint32_t)ldw * 4u; };
+  auto slot = [&](int t, int u) {         // accumulator order inside the tile's footprint
+    return ((uint32_t)(wave * (kTA16 * kTB16) + t * kTB16 + u) * (uint32_t)ldw + (uint32_t)j0) * 4u + (uint32_t)lane * 16u;
+  };
   f32x4 acc[kTA16][kTB16];
   zero_acc<kTA16, kTB16>(acc);
   if (accumulate && whole) {
@@ -806,6 +798,7 @@ __device__ __forceinline__ void dw_tile(
   pa.init(G + v0, ldg, rows, g_cols - v0, wave, lane, wa);
   pb.init(Hc + j0, ldh, rows, d - j0, wave, lane, wb);
   gemm_mainloop_pp<Tile16>(acc, pa, pb, smem, 0, rows, wa, tie_off);
+  lane = lane_index_per_tile();
 #pragma unroll
   for (int t = 0; t < kTA16; ++t)
 #pragma unroll
@@ -850,15 +843,21 @@ __device__ __forceinline__ void dw_tile(
     }
     return;
   }
+  // tiles on a ragged edge: register r of accumulator (t, u) is row wa * 128 + 16 t + 4 (lane / 16) + r, column
+  // wb * 64 + 16 u + lane % 16; rows past the end are dropped by the descriptor's range check, columns masked per lane
 #pragma unroll
-  for (int u = 0; u < kTB16; ++u)
-    if (col_ok[u]) {
+  for (int u = 0; u < kTB16; ++u) {
+    const int j = j0 + wb * 64 + 16 * u + (lane & 15);
+    const uint32_t lane_off = ((uint32_t)(wa * 128 + 4 * (lane >> 4)) * (uint32_t)ldw + (uint32_t)j) * 4u;
+    if (j < d) {
 #pragma unroll
       for (int t = 0; t < kTA16; ++t)
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-          __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[t][u][r]), out, lane_off[u] + row_off(t, r), 0, kNonTemporal);
+          __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[t][u][r]), out,
+                                                lane_off + (uint32_t)(16 * t + r) * (uint32_t)ldw * 4u, 0, kNonTemporal);
     }
+  }
 }
 
 template <bool kStoreOnly>
